@@ -1,0 +1,169 @@
+/*
+ * libfgmp -- FGMP inference hot path for AMD MI355X (gfx950), C ABI.
+ *
+ * FGMP (arxiv 2504.14152) keeps every block of 16 consecutive elements along
+ * the dot-product dimension either in FP8 E4M3 or in NVFP4 (E2M1 values with
+ * one E4M3 scale per block), chosen per block by a Fisher-weighted
+ * quantization-error score compared with a calibrated threshold, and
+ * multiplies activations and weights stored in that unstructured mix with
+ * FP32 accumulation.
+ *
+ * Conventions for every entry point
+ *   - X is M x K (activations), W is N x K (weights), both with K contiguous;
+ *     Y = X * W^T is M x N, FP32, row-major with leading dimension ldy.
+ *     Blocks run along K for both operands (Sec. 1, Sec. 4).  K % 16 == 0.
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned
+ *     by the caller.  Input/packed/workspace pointers must be 16-byte aligned.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  The hot-path calls (quantize_*, gemm,
+ *     quant_gemm_fused, unpack_canonical) never allocate, free or synchronize.
+ *   - Return value: FGMP_OK (0) or a negative fgmp_status_t.  After an error
+ *     the outputs are unspecified; argument errors are detected on the host
+ *     before anything is launched.
+ *   - Inputs must be finite; NaN/Inf inputs give unspecified codes.
+ *   - A packed tensor is an opaque, self-describing device buffer of
+ *     fgmp_packed_bytes(rows, K) bytes (worst case: every block FP8).
+ */
+#ifndef FGMP_H
+#define FGMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int fgmp_status_t;
+enum {
+    FGMP_OK = 0,
+    FGMP_ERR_INVALID_ARG = -1,      /* null pointer, non-positive size, bad enum, S <= 0 */
+    FGMP_ERR_BAD_SHAPE = -2,        /* K % 16 != 0, leading dimension < row length */
+    FGMP_ERR_BAD_ALIGN = -3,        /* pointer or leading dimension not 16-byte aligned */
+    FGMP_ERR_BUFFER_TOO_SMALL = -4, /* packed buffer or workspace smaller than required */
+    FGMP_ERR_UNSUPPORTED = -5,      /* dtype or size outside what the kernels handle */
+    FGMP_ERR_HIP = -6               /* a HIP runtime call failed */
+};
+
+typedef enum { FGMP_F32 = 0, FGMP_BF16 = 1 } fgmp_dtype_t;
+
+/* Host-side summary of a packed tensor (fgmp_packed_info). */
+typedef struct {
+    int64_t rows, K;
+    float tensor_scale;
+    int32_t compact;       /* 1: FP8 upper halves stored densely (weights) */
+    int64_t n_blocks;      /* rows * K / 16 */
+    int64_t n_fp8_blocks;  /* blocks kept in FP8 */
+    int64_t bytes_used;    /* bytes a reader touches / a compact tensor occupies */
+} fgmp_packed_info_t;
+
+/* Library version and the name of the target architecture ("gfx950"). */
+const char *fgmp_version(void);
+
+/* Bytes of a packed rows x K tensor in the worst case (all blocks FP8),
+ * including its header and per-tile tables.  0 on a bad argument. */
+size_t fgmp_packed_bytes(int64_t rows, int64_t K);
+
+/* Bytes of workspace fgmp_gemm / fgmp_quant_gemm_fused need for an
+ * (M x K) * (N x K)^T product.  0 on a bad argument. */
+size_t fgmp_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * Offline weight quantization (Sec. 3.1, Sec. 3.3): score every block of W
+ * with sum_i F_i (w_i - Q_NVFP4(w_i))^2 (Eq. 6), keep it in FP8 iff the score
+ * exceeds `threshold` (Sec. 4.2), else store NVFP4 with a dynamic-max E4M3
+ * block scale, and pack.  The FP8 upper halves are stored compactly, so the
+ * tensor occupies about 9 B per FP4 block and 16 B per FP8 block plus one bit
+ * per block (Sec. 5.4.1).
+ *   W          N x K, dtype dt, leading dimension ldw (elements)
+ *   fisher     FP32 sensitivities: ld_fisher == 0 -> K values, one per input
+ *              channel, shared by all rows; else N x K with that leading dim
+ *   threshold  FP32; +INF keeps every block in FP4, -INF every block in FP8
+ *   tensor_scale  S > 0: stored value = w / S; shared by both formats
+ *   packed_W   out, packed_bytes >= fgmp_packed_bytes(N, K)
+ *   scores_out nullable, N*K/16 FP32 scores, row-major
+ */
+fgmp_status_t fgmp_quantize_weights(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
+                                    const float *fisher, int64_t ld_fisher, float threshold,
+                                    float tensor_scale, void *packed_W, size_t packed_bytes,
+                                    float *scores_out, void *stream);
+
+/*
+ * On-the-fly activation quantization (Sec. 4.2): the same scoring and
+ * decision with one sensitivity per input channel (Sec. 3.1) and a threshold
+ * fixed at calibration time; one pass over X, each block written once in the
+ * precision chosen for it.
+ *   X          M x K, dtype dt, leading dimension ldx (elements)
+ *   fisher_k   K FP32 values
+ *   packed_X   out, packed_bytes >= fgmp_packed_bytes(M, K)
+ *   scores_out nullable, M*K/16 FP32 scores, row-major
+ */
+fgmp_status_t fgmp_quantize_activations(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                        const float *fisher_k, float threshold, float tensor_scale,
+                                        void *packed_X, size_t packed_bytes, float *scores_out,
+                                        void *stream);
+
+/*
+ * Block-mixed-precision GEMM (Sec. 4.1): Y = S_x * S_w * (X^ * W^^T) where X^,
+ * W^ are the stored values (FP8 value, or E2M1 value times its E4M3 block
+ * scale); every block pair is multiplied in the precision its two metadata
+ * bits select and accumulated in FP32.
+ *   packed_X   M x K packed activations; packed_W  N x K packed weights
+ *   Y          out, M x N FP32, leading dimension ldy >= N
+ *   workspace  >= fgmp_workspace_bytes(M, N, K) bytes (may be NULL if that is 0)
+ */
+fgmp_status_t fgmp_gemm(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
+                        float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Quantize X on the fly and multiply, in one call (Sec. 4.2 followed by
+ * Sec. 4.1).  The result equals fgmp_quantize_activations into the workspace
+ * followed by fgmp_gemm.
+ */
+fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                    const float *fisher_k, float threshold, float scale_x,
+                                    const void *packed_W, int64_t N, float *Y, int64_t ldy,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Expand a packed tensor to layout-independent arrays (for tests and tools):
+ *   codes   rows*K bytes: E2M1 code 0..15 (FP4 block) or E4M3 byte (FP8 block)
+ *   scales  rows*K/16 bytes: E4M3 block scale, 0 for FP8 blocks
+ *   mask    rows*K/16 bytes: 1 = FP8 block
+ * Any of the three may be NULL.
+ */
+fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K, uint8_t *codes,
+                                    uint8_t *scales, uint8_t *mask, void *stream);
+
+/*
+ * Offline helpers.  These synchronize `stream` and use host memory.
+ */
+
+/* Read a packed tensor's header and count its FP8 blocks. info_host: host. */
+fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host, void *stream);
+
+/* Threshold for a target fraction of FP8 blocks (Eq. 9): the score below the
+ * round(fraction*J) largest of the J device-resident scores; fraction 0 ->
+ * +INF, 1 -> -INF.  threshold_host: host. */
+fgmp_status_t fgmp_threshold_for_fraction(const float *scores, int64_t J, double fraction,
+                                          float *threshold_host, void *stream);
+
+/*
+ * Conversion self-test hooks: run the library's device-side FP32 -> E2M1
+ * (format 0) or FP32 -> E4M3 (format 1) rounding over every non-negative FP32
+ * bit pattern 0 .. 0x7F800000 (finite values and +INF) and report, per output
+ * code, the smallest and largest input bit pattern that produced it
+ * (min_bits/max_bits: 256 uint32 each, device; untouched codes keep
+ * 0xFFFFFFFF / 0) plus the number of places where the code decreased as the
+ * input grew (violations: 1 uint32, device).
+ * fgmp_decode_table writes the device-side decode of all 256 codes of the
+ * format as FP32 (out: 256 floats, device; E2M1 uses the low nibble).
+ */
+fgmp_status_t fgmp_selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
+                                          uint32_t *violations, void *stream);
+fgmp_status_t fgmp_selftest_decode_table(int format, float *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FGMP_H */

@@ -1,0 +1,134 @@
+// C ABI of libfgmp: argument checks and dispatch.  See include/fgmp.h.
+#include <algorithm>
+#include <vector>
+
+#include "fgmp_internal.hpp"
+
+using namespace fgmp;
+
+static inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+extern "C" {
+
+const char *fgmp_version(void) { return "fgmp 0.1 (gfx950)"; }
+
+size_t fgmp_packed_bytes(int64_t rows, int64_t K)
+{
+    if (rows <= 0 || K <= 0 || K % kBlock != 0) return 0;
+    return (size_t)make_layout(rows, K).total_bytes;
+}
+
+size_t fgmp_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || K % kBlock != 0) return 0;
+    return gemm_workspace_bytes(M, N, K);
+}
+
+fgmp_status_t fgmp_quantize_weights(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
+                                    const float *fisher, int64_t ld_fisher, float threshold,
+                                    float tensor_scale, void *packed_W, size_t packed_bytes,
+                                    float *scores_out, void *stream)
+{
+    return quantize_tensor(W, dt, N, K, ldw, fisher, ld_fisher, threshold, tensor_scale, packed_W,
+                           packed_bytes, scores_out, /*compact=*/true, as_stream(stream));
+}
+
+fgmp_status_t fgmp_quantize_activations(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                        const float *fisher_k, float threshold, float tensor_scale,
+                                        void *packed_X, size_t packed_bytes, float *scores_out,
+                                        void *stream)
+{
+    return quantize_tensor(X, dt, M, K, ldx, fisher_k, /*ld_fisher=*/0, threshold, tensor_scale, packed_X,
+                           packed_bytes, scores_out, /*compact=*/false, as_stream(stream));
+}
+
+fgmp_status_t fgmp_gemm(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
+                        float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_packed(packed_X, M, packed_W, N, K, Y, ldy, workspace, workspace_bytes, as_stream(stream));
+}
+
+fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                    const float *fisher_k, float threshold, float scale_x,
+                                    const void *packed_W, int64_t N, float *Y, int64_t ldy,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return FGMP_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    if ((uintptr_t)workspace % 16 != 0) return FGMP_ERR_BAD_ALIGN;
+    const size_t xbytes = (size_t)make_layout(M, K).total_bytes;
+    if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
+    fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, workspace, xbytes,
+                                       nullptr, /*compact=*/false, as_stream(stream));
+    if (rc != FGMP_OK) return rc;
+    char *rest = static_cast<char *>(workspace) + xbytes;
+    return gemm_packed(workspace, M, packed_W, N, K, Y, ldy, rest, workspace_bytes - xbytes,
+                       as_stream(stream));
+}
+
+fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K, uint8_t *codes,
+                                    uint8_t *scales, uint8_t *mask, void *stream)
+{
+    return unpack_tensor(packed, rows, K, codes, scales, mask, as_stream(stream));
+}
+
+fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host, void *stream)
+{
+    if (!packed || !info_host) return FGMP_ERR_INVALID_ARG;
+    hipStream_t st = as_stream(stream);
+    PackedHeader h;
+    if (hipMemcpyAsync(&h, packed, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return FGMP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return FGMP_ERR_HIP;
+    if (h.magic != kMagic || h.version != kVersion || h.rows <= 0 || h.K <= 0 || h.K % kBlock != 0)
+        return FGMP_ERR_INVALID_ARG;
+    const PackedLayout l = make_layout(h.rows, h.K);
+    std::vector<uint64_t> mbits((size_t)l.n_tiles);
+    if (hipMemcpyAsync(mbits.data(), static_cast<const char *>(packed) + l.off_M, mbits.size() * 8,
+                       hipMemcpyDeviceToHost, st) != hipSuccess)
+        return FGMP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return FGMP_ERR_HIP;
+    int64_t n_hi = 0;
+    for (uint64_t w : mbits) n_hi += __builtin_popcountll(w);
+    info_host->rows = h.rows;
+    info_host->K = h.K;
+    info_host->tensor_scale = h.tensor_scale;
+    info_host->compact = (int32_t)h.compact;
+    info_host->n_blocks = h.rows * (h.K / kBlock);
+    info_host->n_fp8_blocks = n_hi;
+    info_host->bytes_used = (int64_t)h.bytes_used;
+    return FGMP_OK;
+}
+
+fgmp_status_t fgmp_threshold_for_fraction(const float *scores, int64_t J, double fraction,
+                                          float *threshold_host, void *stream)
+{
+    if (!scores || !threshold_host || J <= 0 || !(fraction >= 0.0) || !(fraction <= 1.0))
+        return FGMP_ERR_INVALID_ARG;
+    // Eq. 9 read as: exactly round(fraction * J) blocks score strictly above the threshold
+    const int64_t n_hi = (int64_t)(fraction * (double)J + 0.5);
+    if (n_hi <= 0) { *threshold_host = INFINITY; return FGMP_OK; }
+    if (n_hi >= J) { *threshold_host = -INFINITY; return FGMP_OK; }
+    hipStream_t st = as_stream(stream);
+    std::vector<float> host((size_t)J);
+    if (hipMemcpyAsync(host.data(), scores, (size_t)J * sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return FGMP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return FGMP_ERR_HIP;
+    auto nth = host.begin() + (J - n_hi - 1);
+    std::nth_element(host.begin(), nth, host.end());
+    *threshold_host = *nth;
+    return FGMP_OK;
+}
+
+fgmp_status_t fgmp_selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
+                                          uint32_t *violations, void *stream)
+{
+    return selftest_encode_ranges(format, min_bits, max_bits, violations, as_stream(stream));
+}
+
+fgmp_status_t fgmp_selftest_decode_table(int format, float *out, void *stream)
+{
+    return selftest_decode_table(format, out, as_stream(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,33 @@
+// Internal declarations shared by the translation units of libfgmp.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/fgmp.h"
+#include "fgmp_formats.hpp"
+#include "fgmp_layout.hpp"
+
+namespace fgmp {
+
+// Use the gfx950 conversion instructions in the quantizer.  They are only
+// enabled because the conversion self-test shows them equal to the integer
+// forms for every FP32 input.
+#ifndef FGMP_HW_CVT
+#define FGMP_HW_CVT 1
+#endif
+constexpr bool kUseHwCvt = FGMP_HW_CVT != 0;
+
+fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
+                              const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
+                              size_t packed_bytes, float *scores, bool compact, hipStream_t st);
+fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
+                            uint8_t *mask, hipStream_t st);
+fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
+                          float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
+                                     uint32_t *violations, hipStream_t st);
+fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);
+
+}  // namespace fgmp

@@ -1,0 +1,438 @@
+// FGMP block scoring, precision decision, encoding and packing (Sec. 3.1,
+// Sec. 3.3 "dynamic max", Sec. 4, Sec. 4.2), one 16-element block per lane.
+//
+// Arithmetic per block (every FP32 step is one separately rounded IEEE
+// operation -- this file is compiled with -ffp-contract=off):
+//   amax = max|x_i|; u = amax / (6 S); sc = E4M3(u); d = value(sc) * S
+//   inv_d = 1 / d (0 when sc == 0); q_i = E2M1(x_i * inv_d); xh_i = value(q_i) * d
+//   t_i = ((x_i - xh_i) * (x_i - xh_i)) * F_i                        (Eq. 2, Eq. 6)
+//   score = balanced pairwise tree over t_0..t_15 (adjacent pairs first)
+//   FP8 iff score > T (Sec. 4.2); FP8 codes c_i = E4M3(x_i * (1 / S))  (Sec. 5.1)
+#include "fgmp_internal.hpp"
+
+namespace fgmp {
+
+template <bool kHW> __device__ __forceinline__ uint32_t enc_e4m3(float r)
+{
+    if constexpr (kHW) return e4m3_encode_pair_hw(r, 0.0f) & 0xFFu;
+    else return e4m3_encode_int(r);
+}
+
+// Load 16 consecutive elements as FP32.
+__device__ __forceinline__ void load16(const float *src, float (&x)[16])
+{
+    const float4 *p = reinterpret_cast<const float4 *>(src);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float4 v = p[i];
+        x[4 * i + 0] = v.x; x[4 * i + 1] = v.y; x[4 * i + 2] = v.z; x[4 * i + 3] = v.w;
+    }
+}
+
+__device__ __forceinline__ void load16(const uint16_t *src, float (&x)[16])
+{
+    const uint4 *p = reinterpret_cast<const uint4 *>(src);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        uint4 v = p[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {   // bf16 -> fp32 is a 16-bit shift
+            x[8 * i + 2 * j + 0] = u2f(w[j] << 16);
+            x[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+        }
+    }
+}
+
+struct QuantParams {
+    const void *X;
+    int64_t ldx, rows, nb;
+    const float *fisher;
+    int64_t ld_fisher;
+    float T, S;
+    PackedView out;
+    int64_t n_rt, n_kt;
+    float *scores;
+    int mode;          // kModeStrided / kModeCount / kModeCompact
+    int rt_per_wave;
+};
+
+enum { kModeStrided = 0, kModeCount = 1, kModeCompact = 2 };
+
+// grid.x = K-tiles, grid.y = groups of 4 * rt_per_wave row-tiles; 4 waves per
+// workgroup work on 4 adjacent row-tiles of the same K-tile at a time, so the
+// per-channel sensitivities stay in registers across the loop.
+template <typename Tin, bool kPerElem, bool kHW>
+__global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t kt = blockIdx.x;
+    const int64_t kb = kt * kTileBlocks + (lane & 7);
+    const bool kvalid = kb < p.nb;
+    const int rloc = lane >> 3;
+    const Tin *X = static_cast<const Tin *>(p.X);
+
+    float f[16];
+    if constexpr (!kPerElem) {
+        if (kvalid) load16(p.fisher + kb * kBlock, f);
+        else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) f[i] = 0.0f;
+        }
+    }
+    const float inv_S = 1.0f / p.S;
+    const float S6 = 6.0f * p.S;
+
+    for (int it = 0; it < p.rt_per_wave; ++it) {
+        const int64_t rt = ((int64_t)blockIdx.y * p.rt_per_wave + it) * 4 + wave;
+        if (rt >= p.n_rt) break;
+        const int64_t row = rt * kTileRows + rloc;
+        const bool valid = kvalid && row < p.rows;
+
+        float x[16];
+        if (valid) {
+            load16(X + row * p.ldx + kb * kBlock, x);
+            if constexpr (kPerElem) load16(p.fisher + row * p.ld_fisher + kb * kBlock, f);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                x[i] = 0.0f;
+                if constexpr (kPerElem) f[i] = 0.0f;
+            }
+        }
+
+        // dynamic-max block scale
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(x[i]));
+        const float u = amax / S6;
+        const uint32_t sc = enc_e4m3<kHW>(u);
+        const float d = e4m3_decode_int(sc) * p.S;
+        const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
+
+        // NVFP4 codes, reconstruction, weighted squared error
+        uint32_t q_lo = 0, q_hi = 0;
+        float t[16];
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float r0 = x[i] * inv_d, r1 = x[i + 1] * inv_d;
+            uint32_t byte;
+            float v0, v1;
+            if constexpr (kHW) {
+                byte = e2m1_encode_pair_hw(r0, r1);
+                float2_t v = e2m1_decode_pair_hw(byte);
+                v0 = v[0];
+                v1 = v[1];
+            } else {
+                const uint32_t c0 = e2m1_encode_int(r0), c1 = e2m1_encode_int(r1);
+                byte = c0 | (c1 << 4);
+                v0 = e2m1_decode_int(c0);
+                v1 = e2m1_decode_int(c1);
+            }
+            if (i < 8) q_lo |= byte << (4 * i);
+            else q_hi |= byte << (4 * (i - 8));
+            const float e0 = x[i] - v0 * d, e1 = x[i + 1] - v1 * d;
+            t[i] = (e0 * e0) * f[i];
+            t[i + 1] = (e1 * e1) * f[i + 1];
+        }
+#pragma unroll
+        for (int w = 16; w > 1; w >>= 1)
+#pragma unroll
+            for (int i = 0; i < w / 2; ++i) t[i] = t[2 * i] + t[2 * i + 1];
+        const float score = t[0];
+
+        const bool hi = valid && (score > p.T);
+        const uint64_t ballot = __ballot(hi);
+        const int64_t tile = rt * p.n_kt + kt;
+        if (p.scores != nullptr && valid) p.scores[row * p.nb + kb] = score;
+
+        if (p.mode == kModeCount) {
+            if (lane == 0) p.out.T[tile] = (uint32_t)__popcll(ballot);
+            continue;
+        }
+
+        const uint32_t prefix = (uint32_t)__popcll(ballot & ((1ull << lane) - 1ull));
+        uint32_t hbase;
+        if (p.mode == kModeStrided) {
+            hbase = (uint32_t)(tile * kTileSlots);
+            if (lane == 0) p.out.T[tile] = hbase;
+        } else {
+            hbase = p.out.T[tile];
+        }
+        if (lane == 0) p.out.M[tile] = ballot;
+
+        uint2 lword = make_uint2(q_lo, q_hi);
+        uint32_t sbyte = sc;
+        if (ballot != 0ull) {
+            if (hi) {
+                uint32_t c[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float r0 = x[i] * inv_S, r1 = x[i + 1] * inv_S;
+                    uint32_t two;
+                    if constexpr (kHW) two = e4m3_encode_pair_hw(r0, r1);
+                    else two = e4m3_encode_int(r0) | (e4m3_encode_int(r1) << 8);
+                    c[i / 4] |= two << (8 * (i & 3));
+                }
+                lword = make_uint2(c[0], c[1]);
+                p.out.H[(uint64_t)hbase + prefix] = make_uint2(c[2], c[3]);
+                sbyte = prefix;
+            }
+        }
+        p.out.L[tile * kTileSlots + lane] = lword;
+        p.out.S[tile * kTileSlots + lane] = (uint8_t)sbyte;
+    }
+}
+
+// Exclusive prefix sum over the per-tile FP8 counts in plane T (one workgroup),
+// then the header fields that depend on the total.
+__global__ __launch_bounds__(1024) void scan_tiles_kernel(uint32_t *T, int64_t n_tiles, PackedHeader *hdr,
+                                                           uint64_t off_H)
+{
+    __shared__ uint64_t part[1024];
+    const int tid = threadIdx.x;
+    const int64_t chunk = (n_tiles + 1023) / 1024;
+    const int64_t lo = tid * chunk, hi = (lo + chunk < n_tiles) ? lo + chunk : n_tiles;
+    uint64_t sum = 0;
+    for (int64_t i = lo; i < hi; ++i) sum += T[i];
+    part[tid] = sum;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {   // inclusive Hillis-Steele scan
+        uint64_t v = (tid >= off) ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    uint64_t run = part[tid] - sum;
+    for (int64_t i = lo; i < hi; ++i) {
+        uint32_t c = T[i];
+        T[i] = (uint32_t)run;
+        run += c;
+    }
+    if (tid == 1023) {
+        hdr->h_entries = part[1023];
+        hdr->bytes_used = off_H + part[1023] * 8;
+    }
+}
+
+__global__ void write_header_kernel(PackedHeader *hdr, PackedLayout l, float S, uint32_t compact)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    hdr->magic = kMagic;
+    hdr->version = kVersion;
+    hdr->rows = l.rows;
+    hdr->K = l.K;
+    hdr->tensor_scale = S;
+    hdr->compact = compact;
+    hdr->off_L = l.off_L;
+    hdr->off_S = l.off_S;
+    hdr->off_M = l.off_M;
+    hdr->off_T = l.off_T;
+    hdr->off_H = l.off_H;
+    hdr->h_entries = (uint64_t)l.n_tiles * kTileSlots;
+    hdr->bytes_used = l.total_bytes;
+}
+
+// One wave per tile, one slot per lane: packed -> canonical arrays.
+__global__ __launch_bounds__(256) void unpack_kernel(PackedView v, PackedLayout l, uint8_t *codes,
+                                                      uint8_t *scales, uint8_t *mask)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= l.n_tiles) return;
+    const int64_t rt = tile / l.n_kt, kt = tile % l.n_kt;
+    const int64_t row = rt * kTileRows + (lane >> 3);
+    const int64_t kb = kt * kTileBlocks + (lane & 7);
+    if (row >= l.rows || kb >= l.nb) return;
+    const bool hi = (v.M[tile] >> lane) & 1ull;
+    const uint2 lw = v.L[tile * kTileSlots + lane];
+    const uint32_t sb = v.S[tile * kTileSlots + lane];
+    uint4 out;
+    if (hi) {
+        const uint2 hw = v.H[(uint64_t)v.T[tile] + sb];
+        out = make_uint4(lw.x, lw.y, hw.x, hw.y);
+    } else {
+        // spread 16 nibbles to 16 bytes
+        uint32_t w[4];
+        const uint32_t src[2] = {lw.x, lw.y};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t h = (src[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;  // 4 nibbles
+            w[j] = (h & 0xFu) | ((h & 0xF0u) << 4) | ((h & 0xF00u) << 8) | ((h & 0xF000u) << 12);
+        }
+        out = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    if (codes) *reinterpret_cast<uint4 *>(codes + row * l.K + kb * kBlock) = out;
+    if (scales) scales[row * l.nb + kb] = hi ? 0 : (uint8_t)sb;
+    if (mask) mask[row * l.nb + kb] = hi ? 1 : 0;
+}
+
+// ---- host side ----
+
+static int pick_rt_per_wave(int64_t n_rt)
+{
+    // enough work per wave to amortize the sensitivity loads, enough workgroups to fill 256 CUs
+    if (n_rt >= 4096) return 4;
+    if (n_rt >= 1024) return 2;
+    return 1;
+}
+
+template <typename Tin>
+static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipStream_t st)
+{
+    if (per_elem)
+        hipLaunchKernelGGL((quantize_kernel<Tin, true, kUseHwCvt>), grid, dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((quantize_kernel<Tin, false, kUseHwCvt>), grid, dim3(256), 0, st, p);
+}
+
+fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
+                              const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
+                              size_t packed_bytes, float *scores, bool compact, hipStream_t st)
+{
+    if (!X || !fisher || !packed) return FGMP_ERR_INVALID_ARG;
+    if (rows <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (!(S > 0.0f) || !(S < INFINITY) || T != T) return FGMP_ERR_INVALID_ARG;
+    if (dt != FGMP_F32 && dt != FGMP_BF16) return FGMP_ERR_UNSUPPORTED;
+    if (K % kBlock != 0 || ldx < K || (ld_fisher != 0 && ld_fisher < K)) return FGMP_ERR_BAD_SHAPE;
+    if (rows * (K / kBlock) >= (int64_t)1 << 32) return FGMP_ERR_UNSUPPORTED;
+    const int64_t esz = (dt == FGMP_F32) ? 4 : 2;
+    if (((uintptr_t)X | (uintptr_t)fisher | (uintptr_t)packed | (uintptr_t)scores) % 16 != 0 ||
+        (ldx * esz) % 16 != 0 || (ld_fisher * 4) % 16 != 0)
+        return FGMP_ERR_BAD_ALIGN;
+    const PackedLayout l = make_layout(rows, K);
+    if (packed_bytes < l.total_bytes) return FGMP_ERR_BUFFER_TOO_SMALL;
+
+    QuantParams p;
+    p.X = X; p.ldx = ldx; p.rows = rows; p.nb = l.nb;
+    p.fisher = fisher; p.ld_fisher = ld_fisher;
+    p.T = T; p.S = S;
+    p.out = make_view(packed, l);
+    p.n_rt = l.n_rt; p.n_kt = l.n_kt;
+    p.scores = scores;
+    p.rt_per_wave = pick_rt_per_wave(l.n_rt);
+    const int64_t rt_per_wg = 4 * (int64_t)p.rt_per_wave;
+    const int64_t gy = (l.n_rt + rt_per_wg - 1) / rt_per_wg;
+    if (gy > 65535 || l.n_kt > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)l.n_kt, (unsigned)gy);
+    const bool per_elem = ld_fisher != 0;
+
+    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, st, p.out.hdr, l, S, compact ? 1u : 0u);
+    if (!compact) {
+        p.mode = kModeStrided;
+        if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);
+        else launch_quantize<uint16_t>(p, per_elem, grid, st);
+    } else {
+        QuantParams pc = p;
+        pc.mode = kModeCount;
+        pc.scores = nullptr;
+        if (dt == FGMP_F32) launch_quantize<float>(pc, per_elem, grid, st);
+        else launch_quantize<uint16_t>(pc, per_elem, grid, st);
+        hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(1024), 0, st, p.out.T, l.n_tiles, p.out.hdr,
+                           l.off_H);
+        p.mode = kModeCompact;
+        if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);
+        else launch_quantize<uint16_t>(p, per_elem, grid, st);
+    }
+    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
+fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
+                            uint8_t *mask, hipStream_t st)
+{
+    if (!packed || rows <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    if (((uintptr_t)packed | (uintptr_t)codes) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
+    const PackedLayout l = make_layout(rows, K);
+    const PackedView v = make_view(const_cast<void *>(packed), l);
+    const int64_t nwg = (l.n_tiles + 3) / 4;
+    if (nwg > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)nwg), dim3(256), 0, st, v, l, codes, scales, mask);
+    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
+// ---- conversion self-test kernels ----
+
+template <int kFormat> __device__ __forceinline__ uint32_t selftest_encode(float r)
+{
+    if constexpr (kFormat == 2) return e2m1_encode_int(r);
+    else if constexpr (kFormat == 3) return e4m3_encode_int(r);
+    else if constexpr (kFormat == 4) return e2m1_encode_pair_hw(r, 0.0f) & 0xFu;
+    else return e4m3_encode_pair_hw(r, 0.0f) & 0xFFu;
+}
+
+constexpr uint32_t kLastPattern = 0x7F800000u;   // +INF
+constexpr uint32_t kRunLength = 4096;
+
+template <int kFormat>
+__global__ __launch_bounds__(256) void encode_ranges_kernel(uint32_t *min_bits, uint32_t *max_bits,
+                                                             uint32_t *violations)
+{
+    const uint64_t first = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * kRunLength;
+    if (first > kLastPattern) return;
+    uint64_t last = first + kRunLength - 1;
+    if (last > kLastPattern) last = kLastPattern;
+    uint32_t cur = selftest_encode<kFormat>(u2f((uint32_t)first)) & 0xFFu;
+    uint32_t start = (uint32_t)first;
+    for (uint64_t b = first + 1; b <= last; ++b) {
+        const uint32_t c = selftest_encode<kFormat>(u2f((uint32_t)b)) & 0xFFu;
+        if (c != cur) {
+            atomicMin(&min_bits[cur], start);
+            atomicMax(&max_bits[cur], (uint32_t)(b - 1));
+            if (c < cur) atomicAdd(violations, 1u);
+            cur = c;
+            start = (uint32_t)b;
+        }
+    }
+    atomicMin(&min_bits[cur], start);
+    atomicMax(&max_bits[cur], (uint32_t)last);
+}
+
+__global__ void init_ranges_kernel(uint32_t *min_bits, uint32_t *max_bits, uint32_t *violations)
+{
+    min_bits[threadIdx.x] = 0xFFFFFFFFu;
+    max_bits[threadIdx.x] = 0u;
+    if (threadIdx.x == 0) *violations = 0u;
+}
+
+__global__ void decode_table_kernel(int format, float *out)
+{
+    const uint32_t c = threadIdx.x;
+    float v;
+    switch (format) {
+    case 2: v = e2m1_decode_int(c & 0xFu); break;
+    case 3: v = e4m3_decode_int(c); break;
+    case 4: v = e2m1_decode_pair_hw(c & 0xFu)[0]; break;
+    default: v = e4m3_decode_pair_hw(c)[0]; break;
+    }
+    out[c] = v;
+}
+
+fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
+                                     uint32_t *violations, hipStream_t st)
+{
+    if (!min_bits || !max_bits || !violations) return FGMP_ERR_INVALID_ARG;
+    if (format < 0 || format > 5) return FGMP_ERR_INVALID_ARG;
+    if (format < 2) format += kUseHwCvt ? 4 : 2;   // the form the quantizer uses
+    hipLaunchKernelGGL(init_ranges_kernel, dim3(1), dim3(256), 0, st, min_bits, max_bits, violations);
+    const uint64_t n_threads = ((uint64_t)kLastPattern + kRunLength) / kRunLength;
+    const dim3 grid((unsigned)((n_threads + 255) / 256));
+    switch (format) {
+    case 2: hipLaunchKernelGGL((encode_ranges_kernel<2>), grid, dim3(256), 0, st, min_bits, max_bits, violations); break;
+    case 3: hipLaunchKernelGGL((encode_ranges_kernel<3>), grid, dim3(256), 0, st, min_bits, max_bits, violations); break;
+    case 4: hipLaunchKernelGGL((encode_ranges_kernel<4>), grid, dim3(256), 0, st, min_bits, max_bits, violations); break;
+    default: hipLaunchKernelGGL((encode_ranges_kernel<5>), grid, dim3(256), 0, st, min_bits, max_bits, violations); break;
+    }
+    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
+fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st)
+{
+    if (!out || format < 0 || format > 5) return FGMP_ERR_INVALID_ARG;
+    if (format < 2) format += kUseHwCvt ? 4 : 2;
+    hipLaunchKernelGGL(decode_table_kernel, dim3(1), dim3(256), 0, st, format, out);
+    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
+}  // namespace fgmp

@@ -1,0 +1,220 @@
+"""Thin ctypes binding of libfgmp.so (include/fgmp.h): argument marshalling
+only.  PyTorch supplies device memory and the current HIP stream; every step
+of the path runs in the library's kernels.  There is no fallback: if the
+shared library is missing or a call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+_ERRORS = {-1: "INVALID_ARG", -2: "BAD_SHAPE", -3: "BAD_ALIGN", -4: "BUFFER_TOO_SMALL",
+           -5: "UNSUPPORTED", -6: "HIP_ERROR"}
+_lib = None
+
+
+class FgmpError(RuntimeError):
+    pass
+
+
+class _PackedInfo(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("K", ctypes.c_int64), ("tensor_scale", ctypes.c_float),
+                ("compact", ctypes.c_int32), ("n_blocks", ctypes.c_int64),
+                ("n_fp8_blocks", ctypes.c_int64), ("bytes_used", ctypes.c_int64)]
+
+
+def lib() -> ctypes.CDLL:
+    """Load libfgmp.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.lib_path()
+    if not os.path.exists(path):
+        _build.build()
+    L = ctypes.CDLL(path)
+    vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    L.fgmp_version.restype = ctypes.c_char_p
+    L.fgmp_version.argtypes = []
+    L.fgmp_packed_bytes.restype = sz
+    L.fgmp_packed_bytes.argtypes = [i64, i64]
+    L.fgmp_workspace_bytes.restype = sz
+    L.fgmp_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fgmp_quantize_weights.restype = ctypes.c_int
+    L.fgmp_quantize_weights.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i64, f32, f32, vp, sz, vp, vp]
+    L.fgmp_quantize_activations.restype = ctypes.c_int
+    L.fgmp_quantize_activations.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, sz, vp, vp]
+    L.fgmp_gemm.restype = ctypes.c_int
+    L.fgmp_gemm.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, sz, vp]
+    L.fgmp_quant_gemm_fused.restype = ctypes.c_int
+    L.fgmp_quant_gemm_fused.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, vp, i64,
+                                        vp, sz, vp]
+    L.fgmp_unpack_canonical.restype = ctypes.c_int
+    L.fgmp_unpack_canonical.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    L.fgmp_packed_info.restype = ctypes.c_int
+    L.fgmp_packed_info.argtypes = [vp, ctypes.POINTER(_PackedInfo), vp]
+    L.fgmp_threshold_for_fraction.restype = ctypes.c_int
+    L.fgmp_threshold_for_fraction.argtypes = [vp, i64, ctypes.c_double, ctypes.POINTER(f32), vp]
+    L.fgmp_selftest_encode_ranges.restype = ctypes.c_int
+    L.fgmp_selftest_encode_ranges.argtypes = [ctypes.c_int, vp, vp, vp, vp]
+    L.fgmp_selftest_decode_table.restype = ctypes.c_int
+    L.fgmp_selftest_decode_table.argtypes = [ctypes.c_int, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise FgmpError(f"{what} failed: {_ERRORS.get(rc, rc)}")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise FgmpError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _require_cuda(*tensors) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise FgmpError("all tensors must live on the GPU")
+
+
+@dataclass
+class Packed:
+    """An opaque packed FGMP tensor in device memory."""
+    buf: torch.Tensor   # uint8
+    rows: int
+    K: int
+
+
+def version() -> str:
+    return lib().fgmp_version().decode()
+
+
+def packed_bytes(rows: int, K: int) -> int:
+    return int(lib().fgmp_packed_bytes(rows, K))
+
+
+def workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().fgmp_workspace_bytes(M, N, K))
+
+
+def _alloc_packed(rows: int, K: int, device) -> Packed:
+    n = packed_bytes(rows, K)
+    if n == 0:
+        raise FgmpError("bad packed shape")
+    return Packed(torch.empty(n, dtype=torch.uint8, device=device), rows, K)
+
+
+def quantize_weights(W: torch.Tensor, fisher: torch.Tensor, threshold: float, tensor_scale: float,
+                     want_scores: bool = False, out: Packed | None = None):
+    _require_cuda(W, fisher)
+    N, K = W.shape
+    ldf = 0 if fisher.dim() == 1 else fisher.stride(0)
+    out = out or _alloc_packed(N, K, W.device)
+    scores = torch.empty((N, K // 16), dtype=torch.float32, device=W.device) if want_scores else None
+    rc = lib().fgmp_quantize_weights(_ptr(W), _dtype_code(W), N, K, W.stride(0), _ptr(fisher), ldf,
+                                     float(threshold), float(tensor_scale), _ptr(out.buf), out.buf.numel(),
+                                     _ptr(scores), _stream())
+    _check(rc, "fgmp_quantize_weights")
+    return (out, scores) if want_scores else out
+
+
+def quantize_activations(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, tensor_scale: float,
+                         want_scores: bool = False, out: Packed | None = None):
+    _require_cuda(X, fisher_k)
+    M, K = X.shape
+    out = out or _alloc_packed(M, K, X.device)
+    scores = torch.empty((M, K // 16), dtype=torch.float32, device=X.device) if want_scores else None
+    rc = lib().fgmp_quantize_activations(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                         float(threshold), float(tensor_scale), _ptr(out.buf),
+                                         out.buf.numel(), _ptr(scores), _stream())
+    _check(rc, "fgmp_quantize_activations")
+    return (out, scores) if want_scores else out
+
+
+def gemm(pX: Packed, pW: Packed, out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    if pX.K != pW.K:
+        raise FgmpError("K mismatch")
+    M, N, K = pX.rows, pW.rows, pX.K
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=pX.buf.device)
+    ws_n = 0 if workspace is None else workspace.numel()
+    rc = lib().fgmp_gemm(_ptr(pX.buf), M, _ptr(pW.buf), N, K, _ptr(Y), Y.stride(0), _ptr(workspace), ws_n,
+                         _stream())
+    _check(rc, "fgmp_gemm")
+    return Y
+
+
+def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, scale_x: float, pW: Packed,
+                     out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    _require_cuda(X, fisher_k)
+    M, K = X.shape
+    if K != pW.K:
+        raise FgmpError("K mismatch")
+    N = pW.rows
+    Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(workspace_bytes(M, N, K), dtype=torch.uint8, device=X.device)
+    rc = lib().fgmp_quant_gemm_fused(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                     float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(Y), Y.stride(0),
+                                     _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "fgmp_quant_gemm_fused")
+    return Y
+
+
+def unpack_canonical(p: Packed):
+    """(codes [rows,K] u8, scales [rows,K/16] u8, mask [rows,K/16] u8) on the device."""
+    dev = p.buf.device
+    codes = torch.empty((p.rows, p.K), dtype=torch.uint8, device=dev)
+    scales = torch.empty((p.rows, p.K // 16), dtype=torch.uint8, device=dev)
+    mask = torch.empty((p.rows, p.K // 16), dtype=torch.uint8, device=dev)
+    rc = lib().fgmp_unpack_canonical(_ptr(p.buf), p.rows, p.K, _ptr(codes), _ptr(scales), _ptr(mask), _stream())
+    _check(rc, "fgmp_unpack_canonical")
+    return codes, scales, mask
+
+
+def packed_info(p: Packed) -> dict:
+    info = _PackedInfo()
+    _check(lib().fgmp_packed_info(_ptr(p.buf), ctypes.byref(info), _stream()), "fgmp_packed_info")
+    return {name: getattr(info, name) for name, _ in _PackedInfo._fields_}
+
+
+def threshold_for_fraction(scores: torch.Tensor, fraction: float) -> float:
+    _require_cuda(scores)
+    s = scores.contiguous().view(-1)
+    out = ctypes.c_float()
+    _check(lib().fgmp_threshold_for_fraction(_ptr(s), s.numel(), float(fraction), ctypes.byref(out), _stream()),
+           "fgmp_threshold_for_fraction")
+    return float(out.value)
+
+
+def selftest_encode_ranges(fmt: int, device="cuda"):
+    mn = torch.empty(256, dtype=torch.int32, device=device)
+    mx = torch.empty(256, dtype=torch.int32, device=device)
+    viol = torch.empty(4, dtype=torch.int32, device=device)
+    _check(lib().fgmp_selftest_encode_ranges(fmt, _ptr(mn), _ptr(mx), _ptr(viol), _stream()),
+           "fgmp_selftest_encode_ranges")
+    torch.cuda.synchronize()
+    to_u32 = lambda t: t.cpu().numpy().view("uint32")
+    return to_u32(mn), to_u32(mx), int(to_u32(viol)[0])
+
+
+def selftest_decode_table(fmt: int, device="cuda"):
+    out = torch.empty(256, dtype=torch.float32, device=device)
+    _check(lib().fgmp_selftest_decode_table(fmt, _ptr(out), _stream()), "fgmp_selftest_decode_table")
+    return out.cpu().numpy()
