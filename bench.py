@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the FGMP hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+on-the-fly activation quantization (scoring, FP8/NVFP4 decision, packing)
+followed by the block-mixed-precision GEMM against pre-quantized weights,
+issued as one fgmp_quant_gemm_fused call.  The workload is the Llama-2-7B
+fused QKV projection at 4K context: X 4096 x 4096 bf16 with 1% outlier
+channels, W 12288 x 4096 pre-quantized with 10% FP8 blocks, 10% FP8
+activation blocks.  Inputs are resident in HBM before the timed region.
+
+Prints one JSON line (see the keys below).  `value` is 2*M*N*K divided by the
+time of a whole step.  `roofline` is for the dominant kernel (the GEMM);
+`extra` carries the standalone activation quantizer's GB/s on 16384 x 8192
+and the decode-shape (M <= 32) weight-streaming rates.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "FGMP GEMM TFLOP/s + act-quant GB/s, Llama-2-7B linear shapes, 10% FP8 blocks"
+PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense FP16/BF16 matrix peak
+PEAK_HBM_GBPS = 8000.0
+P_FP8 = 0.10
+
+
+def bytes_per_block(p: float) -> float:
+    """Packed bytes per 16-element block: 9 B (FP4 + scale) or 16 B (FP8) + 1 metadata bit (Sec. 5.4.1)."""
+    return (1.0 - p) * 9.0 + p * 16.0 + 0.125
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(the path would shard over rows of X or rows of W without communication, see DESIGN.md)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2504_14152_amd import fgmp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda"
+    fgmp.lib()  # fail loudly if the HIP library is missing
+
+    def dev_bf16(x32):
+        bits = synth.f32_to_bf16_bits(x32)
+        return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16), bits
+
+    def timed(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters  # ms per call
+
+    # ------------------------------------------------------------ workload (configs[1])
+    M, K, N = 4096, 4096, 12288
+    x32 = synth.activations(M, K, 0, 1)
+    w32 = synth.weights(N, K, 0, 2)
+    fx = synth.fisher_per_channel(K, 0, 3)
+    fw = synth.fisher_per_element(N, K, 0, 4)
+    xd, xbits = dev_bf16(x32)
+    wd, wbits = dev_bf16(w32)
+    xref = synth.bf16_bits_to_f32(xbits)
+    sx = float(synth.default_tensor_scale(xref))
+    sw = float(synth.default_tensor_scale(synth.bf16_bits_to_f32(wbits)))
+    fxd, fwd = torch.from_numpy(fx).to(dev), torch.from_numpy(fw).to(dev)
+    del w32
+
+    # offline: weight scores -> threshold for 10% FP8 -> packed weights; activation threshold calibrated the same way
+    _, sws = fgmp.quantize_weights(wd, fwd, float("inf"), sw, want_scores=True)
+    Tw = fgmp.threshold_for_fraction(sws, P_FP8)
+    pW = fgmp.quantize_weights(wd, fwd, Tw, sw)
+    del sws
+    _, sxs = fgmp.quantize_activations(xd, fxd, float("inf"), sx, want_scores=True)
+    Tx = fgmp.threshold_for_fraction(sxs, P_FP8)
+    del sxs
+    w_info = fgmp.packed_info(pW)
+
+    Y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(fgmp.workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
+    pX = fgmp.quantize_activations(xd, fxd, Tx, sx)
+    x_info = fgmp.packed_info(pX)
+
+    def step():
+        fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW, out=Y, workspace=ws)
+
+    # ------------------------------------------------------------ timed region: K whole steps
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_host0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    t_host = (time.perf_counter() - t_host0) * 1e3 / args.steps
+    ms_step = max(e0.elapsed_time(e1) / args.steps, 1e-6)
+    flops = 2.0 * M * N * K
+    value = flops / (ms_step * 1e-3) / 1e12
+
+    # dominant kernel: the GEMM alone, same launch configuration, events on the launch stream
+    ms_gemm = timed(lambda: fgmp.gemm(pX, pW, out=Y), args.steps, 2)
+    ms_quant = timed(lambda: fgmp.quantize_activations(xd, fxd, Tx, sx, out=pX), args.steps, 2)
+    achieved = flops / (ms_gemm * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel", "achieved": round(achieved, 2),
+                "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
+                "traffic": None, "ms_per_launch": round(ms_gemm, 4)}
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "Llama-2-7B fused QKV prefill (configs[1]): X 4096x4096 bf16, 1% channels x20; "
+                               "W 12288x4096 N(0,0.02) packed FGMP; 10% FP8 blocks in weights and activations; "
+                               "step = fgmp_quant_gemm_fused",
+                   "M": M, "K": K, "N": N, "fp8_fraction_w": round(w_info["n_fp8_blocks"] / w_info["n_blocks"], 4),
+                   "fp8_fraction_x": round(x_info["n_fp8_blocks"] / x_info["n_blocks"], 4),
+                   "packed_w_bytes": w_info["bytes_used"]},
+        "roofline": roofline,
+    }
+
+    extra = {"ms_quantize_x": round(ms_quant, 4), "ms_gemm": round(ms_gemm, 4), "host_ms_per_step": round(t_host, 4)}
+    x_bytes = M * K * 2 + (M * K // 16) * bytes_per_block(P_FP8)
+    extra["act_quant_prefill_GBps"] = round(x_bytes / (ms_quant * 1e-3) / 1e9, 1)
+
+    if not args.no_extra:
+        # standalone activation quantizer, 16384 x 8192 bf16 (configs[4]); HBM-bound
+        Mq, Kq = 16384, 8192
+        xq = synth.activations(Mq, Kq, 0, 11)
+        xqd, xqbits = dev_bf16(xq)
+        sq = float(synth.default_tensor_scale(synth.bf16_bits_to_f32(xqbits)))
+        del xq, xqbits
+        fq = torch.from_numpy(synth.fisher_per_channel(Kq, 0, 12)).to(dev)
+        _, sc = fgmp.quantize_activations(xqd, fq, float("inf"), sq, want_scores=True)
+        Tq = fgmp.threshold_for_fraction(sc, P_FP8)
+        del sc
+        pq = fgmp.quantize_activations(xqd, fq, Tq, sq)
+        ms_q = timed(lambda: fgmp.quantize_activations(xqd, fq, Tq, sq, out=pq), 20, 3)
+        qbytes = Mq * Kq * 2 + (Mq * Kq // 16) * bytes_per_block(P_FP8)
+        gbps = qbytes / (ms_q * 1e-3) / 1e9
+        extra["act_quant_16384x8192"] = {"ms": round(ms_q, 4), "GBps": round(gbps, 1),
+                                         "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
+                                         "algorithmic_bytes": int(qbytes)}
+        del xqd, pq
+        # decode shapes: M tokens against the packed QKV weights (weight streaming; cache-warm, same buffers)
+        dec = {}
+        for Md in (1, 8, 32):
+            xs = xd[:Md].contiguous()
+            pXd = fgmp.quantize_activations(xs, fxd, Tx, sx)
+            Yd = torch.empty((Md, N), dtype=torch.float32, device=dev)
+            ms_d = timed(lambda: fgmp.gemm(pXd, pW, out=Yd), 20, 3)
+            dbytes = (N * K // 16) * bytes_per_block(P_FP8) + (Md * K // 16) * bytes_per_block(P_FP8) + Md * N * 4
+            dec[f"M{Md}"] = {"ms": round(ms_d, 4), "GBps": round(dbytes / (ms_d * 1e-3) / 1e9, 1),
+                             "note": "cache-warm (same weight buffer every launch)"}
+        extra["decode_qkv"] = dec
+    out["extra"] = extra
+
+    # ------------------------------------------------------------ CPU baseline: the oracle on a bounded sample
+    if not args.no_cpu_baseline:
+        from oracle import fgmp_oracle as orc
+        rows, cols = 256, 3072
+        wref = synth.bf16_bits_to_f32(wbits[:cols])
+        qw = orc.quantize(wref, fw[:cols], Tw, sw)             # offline, not timed
+        aw = orc.dequantize(qw["codes"], qw["scales"], qw["mask"])
+        t0 = time.perf_counter()
+        qx = orc.quantize(xref[:rows], fx, Tx, sx)
+        ax = orc.dequantize(qx["codes"], qx["scales"], qx["mask"])
+        orc.gemm(ax, sx, aw, sw)
+        dt = time.perf_counter() - t0
+        cpu_flops = 2.0 * rows * cols * K
+        out["cpu_baseline"] = {"value": round(cpu_flops / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {rows} rows of X (quantize + dequantize) times the first {cols} "
+                                         f"weight rows at full K={K}, fp64; {dt:.1f} s; rate counted as 2*rows*cols*K / time",
+                               "seconds": round(dt, 2)}
+
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

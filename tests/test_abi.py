@@ -1,0 +1,50 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every
+symbol the public header declares, and rejects bad arguments before launching
+anything."""
+import ctypes
+import os
+import re
+
+from paper_2504_14152_amd import build, fgmp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fgmp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fgmp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(build.lib_path()):
+        build.build()
+    lib = ctypes.CDLL(build.lib_path())
+    names = _declared_symbols()
+    assert {"fgmp_quantize_weights", "fgmp_quantize_activations", "fgmp_gemm", "fgmp_quant_gemm_fused",
+            "fgmp_unpack_canonical"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in fgmp.h but not exported"
+
+
+def test_sizes_and_host_side_argument_checks():
+    assert fgmp.version().endswith("(gfx950)")
+    # 8 x 128 tiles: header + 512 B + 64 B + 8 B + 4 B + 512 B per tile, planes 256-byte aligned
+    assert fgmp.packed_bytes(8, 128) == 256 + 512 + 256 + 256 + 256 + 512
+    assert fgmp.packed_bytes(8, 24) == 0 and fgmp.packed_bytes(0, 16) == 0
+    n_blocks = 4096 * 4096 // 16
+    # worst case: 8 + 8 B values, the scale-or-index byte, 1 mask bit, 4 B of tile table per 64 blocks
+    assert 16.125 * n_blocks <= fgmp.packed_bytes(4096, 4096) <= (17 + 0.125 + 0.0625) * n_blocks + 2048
+    assert fgmp.workspace_bytes(4096, 12288, 4096) >= fgmp.packed_bytes(4096, 4096)
+    L = fgmp.lib()
+    assert L.fgmp_quantize_activations(None, 0, 8, 128, 128, None, 0.0, 1.0, None, 0, None, None) == -1
+    assert L.fgmp_gemm(None, 1, None, 1, 16, None, 1, None, 0, None) == -1
+    assert L.fgmp_gemm(256, 1, 256, 1, 24, 256, 1, None, 0, None) == -2
+    assert L.fgmp_unpack_canonical(None, 1, 16, None, None, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "one GPU" in res.stderr
