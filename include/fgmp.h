@@ -110,7 +110,9 @@ fgmp_status_t fgmp_quantize_activations(const void *X, fgmp_dtype_t dt, int64_t 
  * bits select and accumulated in FP32.
  *   packed_X   M x K packed activations; packed_W  N x K packed weights
  *   Y          out, M x N FP32, leading dimension ldy >= N
- *   workspace  >= fgmp_workspace_bytes(M, N, K) bytes (may be NULL if that is 0)
+ *   workspace  >= fgmp_workspace_bytes(M, N, K) bytes of scratch (the decoded
+ *              FP16 operands live here during the call)
+ * Operands whose headers do not match (M, K) / (N, K) are treated as zeros.
  */
 fgmp_status_t fgmp_gemm(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
                         float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);

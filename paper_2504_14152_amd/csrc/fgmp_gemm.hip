@@ -5,6 +5,10 @@
 // significant bits, magnitudes 2^-10 .. 2688), multiplied on the matrix
 // cores and accumulated in FP32, which is what the paper's four dot-product
 // units followed by the FP32 partial-sum adder compute.
+//
+// Prefill path: a decode pass expands both packed operands to FP16 in the
+// caller's workspace (HBM-bound, a few percent of the GEMM time at these
+// shapes), then a 256x256x64-tiled MFMA kernel multiplies them.
 #include "fgmp_internal.hpp"
 
 namespace fgmp {
@@ -12,50 +16,74 @@ namespace fgmp {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128, kBN = 128, kBK = kTileK;   // workgroup tile; one K-tile per step
-constexpr int kLdsK = kBK + 8;                       // halves per LDS row (16 B pad against bank conflicts)
 constexpr int kNumXcd = 8;
 
-// Decode the block in slot `lane` of `tile` to 16 FP16 values.
-__device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, int lane, _Float16 (&out)[16])
+// ---------------------------------------------------------------------------
+// packed -> FP16 decode
+// ---------------------------------------------------------------------------
+
+// Decode the block in slot `lane` of `tile` to 16 FP16 values with the gfx950
+// conversion instructions (exact for every code; first element in the low
+// nibble / byte).
+__device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, int lane, half2_t (&out)[8])
 {
     const uint2 lw = v.L[tile * kTileSlots + lane];
     const uint32_t sb = v.S[tile * kTileSlots + lane];
     const uint64_t mbits = v.M[tile];
     if ((mbits >> lane) & 1ull) {
         const uint2 hw = v.H[(uint64_t)v.T[tile] + sb];
-        const uint32_t w[4] = {lw.x, lw.y, hw.x, hw.y};
-#pragma unroll
-        for (int i = 0; i < 16; ++i) out[i] = (_Float16)e4m3_decode_int((w[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+        out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.x, 1.0f, false);
+        out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.x, 1.0f, true);
+        out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.y, 1.0f, false);
+        out[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.y, 1.0f, true);
+        out[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.x, 1.0f, false);
+        out[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.x, 1.0f, true);
+        out[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.y, 1.0f, false);
+        out[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.y, 1.0f, true);
     } else {
-        const float s = e4m3_decode_int(sb);
-        const uint32_t w[2] = {lw.x, lw.y};
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            out[i] = (_Float16)(e2m1_decode_int((w[i >> 3] >> (4 * (i & 7))) & 0xFu) * s);
+        const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sb | (sb << 8), 1.0f, false);
+        out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 0) * s;
+        out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 1) * s;
+        out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 2) * s;
+        out[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 3) * s;
+        out[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 0) * s;
+        out[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 1) * s;
+        out[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 2) * s;
+        out[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 3) * s;
     }
 }
 
-// Decode 16 row-tiles (128 rows) x one K-tile of a packed operand into LDS.
-__device__ __forceinline__ void decode_operand(const PackedView &v, const PackedLayout &l, int64_t rt0,
-                                               int64_t kt, _Float16 *lds, int wave, int lane)
+// One wave per 8 x 128 tile of the zero-padded FP16 matrix out[rows_pad][ld].
+__global__ __launch_bounds__(256) void decode_f16_kernel(PackedView v, PackedLayout l, _Float16 *out, int64_t ld,
+                                                          int64_t n_rt_pad)
 {
-#pragma unroll 1
-    for (int i = 0; i < 4; ++i) {
-        const int rtl = wave + 4 * i;                // row-tile within the workgroup tile
-        const int64_t rt = rt0 + rtl;
-        _Float16 vals[16];
-        if (rt < l.n_rt) {
-            decode_slot(v, rt * l.n_kt + kt, lane, vals);
-        } else {
+    const int lane = threadIdx.x & 63;
+    const int64_t id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (id >= n_rt_pad * l.n_kt) return;
+    const int64_t rt = id / l.n_kt, kt = id % l.n_kt;
+    half2_t vals[8];
+    // an operand whose header does not describe the shape this launch assumes decodes to zeros
+    const bool header_ok = v.hdr->magic == kMagic && v.hdr->rows == l.rows && v.hdr->K == l.K;
+    if (rt < l.n_rt && header_ok) {
+        decode_slot(v, rt * l.n_kt + kt, lane, vals);
+    } else {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) vals[j] = (_Float16)0.0f;
-        }
-        _Float16 *dst = lds + (rtl * kTileRows + (lane >> 3)) * kLdsK + (lane & 7) * kBlock;
-        *reinterpret_cast<half8_t *>(dst) = *reinterpret_cast<half8_t *>(&vals[0]);
-        *reinterpret_cast<half8_t *>(dst + 8) = *reinterpret_cast<half8_t *>(&vals[8]);
+        for (int j = 0; j < 8; ++j) vals[j] = half2_t{(_Float16)0.0f, (_Float16)0.0f};
     }
+    _Float16 *dst = out + (rt * kTileRows + (lane >> 3)) * ld + kt * kTileK + (lane & 7) * kBlock;
+    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(vals);
+    d4[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    d4[1] = make_uint4(w[4], w[5], w[6], w[7]);
 }
+
+// ---------------------------------------------------------------------------
+// dense FP16 x FP16 -> FP32 MFMA kernel, A [Mp][ld], B [Np][ld], both K-major
+// ---------------------------------------------------------------------------
+
+constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kRowBytes = kBK * 2;               // 128 B of K per tile row, 8 chunks of 16 B
+constexpr int kTileBytes = kBM * kRowBytes;      // 32 KB per operand per stage
 
 // Map the hardware workgroup id (dispatched round-robin over the 8 XCDs) to a
 // logical tile id so that each XCD works on a contiguous range of tiles, then
@@ -78,89 +106,150 @@ __device__ __forceinline__ void tile_coords(int64_t n_tm, int64_t n_tn, int64_t 
     tn = in_g / gsz;
 }
 
-__global__ __launch_bounds__(256, 2) void gemm_kernel(PackedView A, PackedLayout la, PackedView B,
-                                                       PackedLayout lb, float *Y, int64_t ldy, int64_t M,
-                                                       int64_t N, int64_t n_tm, int64_t n_tn)
+// LDS tile layout: row r of a 256 x 64 operand tile occupies 128 contiguous
+// bytes; its 16-byte chunk q (8 halves of K) sits at chunk position
+// q ^ (r & 7).  The swizzle is applied on the global side of the direct
+// global->LDS loads (a wave's load always fills 1 KB of consecutive LDS), and
+// makes the MFMA operand reads (32 rows x one chunk) bank-conflict free.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void global_void_t;
+
+__global__ __launch_bounds__(256, 1) void gemm_f16_kernel(const _Float16 *__restrict__ A,
+                                                           const _Float16 *__restrict__ B, int64_t ld, int nk,
+                                                           float *__restrict__ Y, int64_t ldy, int64_t M,
+                                                           int64_t N, int64_t n_tm, int64_t n_tn,
+                                                           const PackedHeader *ha, const PackedHeader *hb)
 {
-    __shared__ __attribute__((aligned(16))) _Float16 As[kBM * kLdsK];
-    __shared__ __attribute__((aligned(16))) _Float16 Bs[kBN * kLdsK];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;   // 2 x 2 waves, 64 x 64 each
-    // refuse operands whose headers do not describe the shapes this launch assumes
-    if (A.hdr->magic != kMagic || B.hdr->magic != kMagic || A.hdr->rows != la.rows || A.hdr->K != la.K ||
-        B.hdr->rows != lb.rows || B.hdr->K != lb.K)
-        return;
+    __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];   // [stage][operand]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;   // 2 x 2 waves, 128 x 128 each
     int64_t tm, tn;
     tile_coords(n_tm, n_tn, tm, tn);
 
-    float16_t acc[2][2];
+    // direct global -> LDS: wave-load j (j = 4 i + wave, i = 0..7) fills tile rows 8 j .. 8 j + 7;
+    // lane (r = lane / 8, c = lane % 8) fetches global chunk c ^ r of its row
+    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    const char *ga = reinterpret_cast<const char *>(A + (tm * kBM + wave * 8 + lr) * ld) + lc * 16;
+    const char *gb = reinterpret_cast<const char *>(B + (tn * kBN + wave * 8 + lr) * ld) + lc * 16;
+    const int64_t row_step = 32 * ld * 2;   // bytes between wave-loads i and i + 1
+
+    auto issue_loads = [&](int kt, int stage) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_global_load_lds((global_void_t *)(ga + i * row_step + (int64_t)kt * kRowBytes),
+                                             (lds_void_t *)&lds[stage][0][(4 * i + wave) * 1024], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_void_t *)(gb + i * row_step + (int64_t)kt * kRowBytes),
+                                             (lds_void_t *)&lds[stage][1][(4 * i + wave) * 1024], 16, 0, 0);
+        }
+    };
+
+    float16_t acc[4][4];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-    for (int64_t kt = 0; kt < la.n_kt; ++kt) {
-        decode_operand(A, la, tm * (kBM / kTileRows), kt, As, wave, lane);
-        decode_operand(B, lb, tn * (kBN / kTileRows), kt, Bs, wave, lane);
-        __syncthreads();
+    // operand fragment of lane: row (lane & 31) of a 32-row group, K chunk 2 kk + (lane >> 5)
+    int frag_off[4];
 #pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            half8_t a[2], b[2];
+    for (int kk = 0; kk < 4; ++kk)
+        frag_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ (lane & 7)) << 4);
+
+    issue_loads(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70 & 0);   // vmcnt(0)
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int st = kt & 1;
+        if (kt + 1 < nk) issue_loads(kt + 1, st ^ 1);
+        const char *la = &lds[st][0][wm * 128 * kRowBytes], *lb = &lds[st][1][wn * 128 * kRowBytes];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                a[i] = *reinterpret_cast<const half8_t *>(&As[(wm * 64 + i * 32 + frag_row) * kLdsK + kk * 16 + frag_k]);
-                b[i] = *reinterpret_cast<const half8_t *>(&Bs[(wn * 64 + i * 32 + frag_row) * kLdsK + kk * 16 + frag_k]);
+        for (int kk = 0; kk < 4; ++kk) {
+            half8_t a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] = *reinterpret_cast<const half8_t *>(la + i * 32 * kRowBytes + frag_off[kk]);
+                b[i] = *reinterpret_cast<const half8_t *>(lb + i * 32 * kRowBytes + frag_off[kk]);
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+        __builtin_amdgcn_s_waitcnt(0);   // the next stage has landed in LDS
         __syncthreads();
     }
 
     // per-tensor scales are applied once, after accumulation
-    const float ss = A.hdr->tensor_scale * B.hdr->tensor_scale;
+    const float ss = ha->tensor_scale * hb->tensor_scale;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t col = tn * kBN + wn * 64 + j * 32 + (lane & 31);
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = tn * kBN + wn * 128 + j * 32 + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t row = tm * kBM + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int64_t row = tm * kBM + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
             }
         }
 }
 
+static inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct GemmWorkspace {
+    int64_t ld, Mp, Np;
+    size_t off_a, off_b, total;
+};
+
+static GemmWorkspace gemm_ws_layout(int64_t M, int64_t N, int64_t K)
+{
+    GemmWorkspace w;
+    w.ld = round_up(K, kTileK);
+    w.Mp = round_up(M, kBM);
+    w.Np = round_up(N, kBN);
+    w.off_a = 0;
+    w.off_b = (size_t)align_up((uint64_t)w.Mp * w.ld * 2, 256);
+    w.total = w.off_b + (size_t)align_up((uint64_t)w.Np * w.ld * 2, 256);
+    return w;
+}
+
+size_t gemm_only_workspace_bytes(int64_t M, int64_t N, int64_t K) { return gemm_ws_layout(M, N, K).total; }
+
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    (void)N;
-    // room for the packed activations of the fused call
-    return (size_t)make_layout(M, K).total_bytes;
+    // the fused call also keeps the packed activations here
+    return (size_t)make_layout(M, K).total_bytes + gemm_only_workspace_bytes(M, N, K);
 }
 
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
                           float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st)
 {
-    (void)workspace;
-    (void)workspace_bytes;
-    if (!packed_X || !packed_W || !Y) return FGMP_ERR_INVALID_ARG;
+    if (!packed_X || !packed_W || !Y || !workspace) return FGMP_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (K % kBlock != 0 || ldy < N) return FGMP_ERR_BAD_SHAPE;
-    if (((uintptr_t)packed_X | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
+    if (((uintptr_t)packed_X | (uintptr_t)packed_W | (uintptr_t)Y | (uintptr_t)workspace) % 16 != 0)
+        return FGMP_ERR_BAD_ALIGN;
+    const GemmWorkspace w = gemm_ws_layout(M, N, K);
+    if (workspace_bytes < w.total) return FGMP_ERR_BUFFER_TOO_SMALL;
     const PackedLayout la = make_layout(M, K), lb = make_layout(N, K);
     const PackedView A = make_view(const_cast<void *>(packed_X), la);
     const PackedView B = make_view(const_cast<void *>(packed_W), lb);
-    const int64_t n_tm = (M + kBM - 1) / kBM, n_tn = (N + kBN - 1) / kBN;
-    if (n_tm * n_tn > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(gemm_kernel, dim3((unsigned)(n_tm * n_tn)), dim3(256), 0, st, A, la, B, lb, Y, ldy, M,
-                       N, n_tm, n_tn);
+    _Float16 *a16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
+    _Float16 *b16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_b);
+    const int64_t n_tm = w.Mp / kBM, n_tn = w.Np / kBN;
+    const int64_t da = (w.Mp / kTileRows) * la.n_kt, db = (w.Np / kTileRows) * lb.n_kt;
+    if (n_tm * n_tn > 0x7FFFFFFF || (da + 3) / 4 > 0x7FFFFFFF || (db + 3) / 4 > 0x7FFFFFFF)
+        return FGMP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((da + 3) / 4)), dim3(256), 0, st, A, la, a16, w.ld,
+                       w.Mp / kTileRows);
+    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((db + 3) / 4)), dim3(256), 0, st, B, lb, b16, w.ld,
+                       w.Np / kTileRows);
+    hipLaunchKernelGGL(gemm_f16_kernel, dim3((unsigned)(n_tm * n_tn)), dim3(256), 0, st, a16, b16, w.ld,
+                       (int)(w.ld / kBK), Y, ldy, M, N, n_tm, n_tn, A.hdr, B.hdr);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }
 

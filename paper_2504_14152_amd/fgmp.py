@@ -153,7 +153,9 @@ def gemm(pX: Packed, pW: Packed, out: torch.Tensor | None = None, workspace: tor
         raise FgmpError("K mismatch")
     M, N, K = pX.rows, pW.rows, pX.K
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=pX.buf.device)
-    ws_n = 0 if workspace is None else workspace.numel()
+    if workspace is None:
+        workspace = torch.empty(workspace_bytes(M, N, K), dtype=torch.uint8, device=pX.buf.device)
+    ws_n = workspace.numel()
     rc = lib().fgmp_gemm(_ptr(pX.buf), M, _ptr(pW.buf), N, K, _ptr(Y), Y.stride(0), _ptr(workspace), ws_n,
                          _stream())
     _check(rc, "fgmp_gemm")
