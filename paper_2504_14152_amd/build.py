@@ -20,10 +20,11 @@ def lib_path() -> str:
     return LIB
 
 
-def build(verbose: bool = False, extra_flags: list[str] | None = None) -> str:
+def build(verbose: bool = False, extra_flags: list[str] | None = None, out: str | None = None) -> str:
     """Compile every source for gfx950 and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    build_dir = os.path.join(HERE, "_build")
+    out = out or LIB
+    build_dir = os.path.join(HERE, "_build", os.path.basename(out).replace(".so", ""))
     os.makedirs(build_dir, exist_ok=True)
     flags = FLAGS + (extra_flags or [])
 
@@ -43,11 +44,11 @@ def build(verbose: bool = False, extra_flags: list[str] | None = None) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

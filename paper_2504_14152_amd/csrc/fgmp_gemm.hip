@@ -108,47 +108,73 @@ __device__ __forceinline__ void tile_coords(int64_t n_tm, int64_t n_tn, int64_t 
 
 // LDS tile layout: row r of a 256 x 64 operand tile occupies 128 contiguous
 // bytes; its 16-byte chunk q (8 halves of K) sits at chunk position
-// q ^ (r & 7).  The swizzle is applied on the global side of the direct
-// global->LDS loads (a wave's load always fills 1 KB of consecutive LDS), and
-// makes the MFMA operand reads (32 rows x one chunk) bank-conflict free.
+// q ^ ((r >> 1) & 7).  The swizzle is applied on the global side of the direct
+// global->LDS loads (a wave's load always fills 1 KB of consecutive LDS).  The
+// LDS serves 256 B (64 banks) per cycle, i.e. 16 lanes of a 16-byte read: 16
+// consecutive rows reading the same chunk then touch 16 different 16-byte
+// bank groups (measured: no bank-conflict cycles; with q ^ (r & 7) half of
+// the LDS cycles were conflicts).
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void global_void_t;
 
-__global__ __launch_bounds__(256, 1) void gemm_f16_kernel(const _Float16 *__restrict__ A,
-                                                           const _Float16 *__restrict__ B, int64_t ld, int nk,
-                                                           float *__restrict__ Y, int64_t ldy, int64_t M,
-                                                           int64_t N, int64_t n_tm, int64_t n_tn,
-                                                           const PackedHeader *ha, const PackedHeader *hb)
+// Scheduling hint for one pipeline phase: spread its kReads LDS reads (and
+// 2 * kVmem global->LDS loads) evenly between its kMfma MFMAs.
+template <int G, int kReads, int kMfma, int kVmem> __device__ __forceinline__ void interleave_phase()
 {
+    if constexpr (G < kReads) {
+        if constexpr (G < kVmem) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, (kMfma * (G + 1)) / kReads - (kMfma * G) / kReads, 0);
+        interleave_phase<G + 1, kReads, kMfma, kVmem>();
+    }
+}
+
+// kWM x kWN waves per workgroup; each wave owns a (256 / kWM) x (256 / kWN)
+// piece of the tile as TM x TN MFMA tiles of 32 x 32.
+template <int kWM, int kWN>
+__global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float16 *__restrict__ A,
+                                                                     const _Float16 *__restrict__ B, int64_t ld,
+                                                                     int nk, float *__restrict__ Y, int64_t ldy,
+                                                                     int64_t M, int64_t N, int64_t n_tm,
+                                                                     int64_t n_tn, const PackedHeader *ha,
+                                                                     const PackedHeader *hb)
+{
+    constexpr int kWaves = kWM * kWN;
+    constexpr int TM = kBM / (32 * kWM), TN = kBN / (32 * kWN);
+    constexpr int kLoads = 32 / kWaves;          // 1 KB wave-loads per operand per wave per K-step
     __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];   // [stage][operand]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;   // 2 x 2 waves, 128 x 128 each
+    const int wm = wave / kWN, wn = wave % kWN;
     int64_t tm, tn;
     tile_coords(n_tm, n_tn, tm, tn);
 
-    // direct global -> LDS: wave-load j (j = 4 i + wave, i = 0..7) fills tile rows 8 j .. 8 j + 7;
-    // lane (r = lane / 8, c = lane % 8) fetches global chunk c ^ r of its row
-    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    // direct global -> LDS: wave-load j (j = kWaves i + wave) fills tile rows 8 j .. 8 j + 7;
+    // lane (lr = lane / 8, c = lane % 8) fetches global chunk c ^ swizzle(row) of its row;
+    // rows of successive i differ by a multiple of 16, which leaves the swizzle unchanged
+    const int lr = lane >> 3, lc = (lane & 7) ^ (((wave * 8 + lr) >> 1) & 7);
     const char *ga = reinterpret_cast<const char *>(A + (tm * kBM + wave * 8 + lr) * ld) + lc * 16;
     const char *gb = reinterpret_cast<const char *>(B + (tn * kBN + wave * 8 + lr) * ld) + lc * 16;
-    const int64_t row_step = 32 * ld * 2;   // bytes between wave-loads i and i + 1
+    const int64_t row_step = kWaves * 8 * ld * 2;   // bytes between wave-loads i and i + 1
 
     auto issue_loads = [&](int kt, int stage) {
+#ifdef FGMP_DBG_NOLOAD
+        if (kt > 1) return;
+#endif
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kLoads; ++i) {
             __builtin_amdgcn_global_load_lds((global_void_t *)(ga + i * row_step + (int64_t)kt * kRowBytes),
-                                             (lds_void_t *)&lds[stage][0][(4 * i + wave) * 1024], 16, 0, 0);
+                                             (lds_void_t *)&lds[stage][0][(kWaves * i + wave) * 1024], 16, 0, 0);
             __builtin_amdgcn_global_load_lds((global_void_t *)(gb + i * row_step + (int64_t)kt * kRowBytes),
-                                             (lds_void_t *)&lds[stage][1][(4 * i + wave) * 1024], 16, 0, 0);
+                                             (lds_void_t *)&lds[stage][1][(kWaves * i + wave) * 1024], 16, 0, 0);
         }
     };
 
-    float16_t acc[4][4];
+    float16_t acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
@@ -156,47 +182,84 @@ __global__ __launch_bounds__(256, 1) void gemm_f16_kernel(const _Float16 *__rest
     int frag_off[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-        frag_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ (lane & 7)) << 4);
+        frag_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
+    auto read_frags = [&](int stage, int kk, half8_t (&a)[TM], half8_t (&b)[TN]) {
+        const char *la = &lds[stage][0][wm * (TM * 32) * kRowBytes], *lb = &lds[stage][1][wn * (TN * 32) * kRowBytes];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const half8_t *>(la + i * 32 * kRowBytes + frag_off[kk]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const half8_t *>(lb + j * 32 * kRowBytes + frag_off[kk]);
+    };
+    auto mfma_block = [&](const half8_t (&a)[TM], const half8_t (&b)[TN]) {
+#ifdef FGMP_DBG_NOMFMA
+        acc[0][0][0] += (float)a[0][0] * (float)b[0][0] + (float)a[TM - 1][7] * (float)b[TN - 1][7];
+        return;
+#endif
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int kReads = TM + TN, kMfma = TM * TN;
+
+    // Software pipeline.  LDS holds two K-steps; the fragments of the next
+    // 16-wide K slice are read while the MFMAs of the current one run.
+    // Before the last slice of a K-step every wave has finished reading the
+    // current stage, so that is where the barrier sits: after it the other
+    // stage (filled by loads issued one K-step earlier) is visible, and the
+    // stage just consumed is refilled with the K-step after next.
+    half8_t fa[2][TM], fb[2][TN];
     issue_loads(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70 & 0);   // vmcnt(0)
+    issue_loads(nk > 1 ? 1 : 0, 1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    read_frags(0, 0, fa[0], fb[0]);
     for (int kt = 0; kt < nk; ++kt) {
         const int st = kt & 1;
-        if (kt + 1 < nk) issue_loads(kt + 1, st ^ 1);
-        const char *la = &lds[st][0][wm * 128 * kRowBytes], *lb = &lds[st][1][wn * 128 * kRowBytes];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            half8_t a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = *reinterpret_cast<const half8_t *>(la + i * 32 * kRowBytes + frag_off[kk]);
-                b[i] = *reinterpret_cast<const half8_t *>(lb + i * 32 * kRowBytes + frag_off[kk]);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        __builtin_amdgcn_s_waitcnt(0);   // the next stage has landed in LDS
+        read_frags(st, 1, fa[1], fb[1]);
+        mfma_block(fa[0], fb[0]);
+        interleave_phase<0, kReads, kMfma, 0>();
+        read_frags(st, 2, fa[0], fb[0]);
+        mfma_block(fa[1], fb[1]);
+        interleave_phase<0, kReads, kMfma, 0>();
+        read_frags(st, 3, fa[1], fb[1]);
+        mfma_block(fa[0], fb[0]);
+        interleave_phase<0, kReads, kMfma, 0>();
+        __builtin_amdgcn_s_waitcnt(0);   // own LDS reads done, own global->LDS loads landed
         __syncthreads();
+        // the last two iterations reload the final K-step, which nobody reads again
+        issue_loads(kt + 2 < nk ? kt + 2 : nk - 1, st);
+        read_frags(st ^ 1, 0, fa[0], fb[0]);
+        mfma_block(fa[1], fb[1]);
+        interleave_phase<0, kReads, kMfma, kLoads>();
     }
+    __builtin_amdgcn_s_waitcnt(0);
 
     // per-tensor scales are applied once, after accumulation
     const float ss = ha->tensor_scale * hb->tensor_scale;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t col = tn * kBN + wn * 128 + j * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = tn * kBN + wn * (TN * 32) + j * 32 + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t row = tm * kBM + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int64_t row = tm * kBM + wm * (TM * 32) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+#ifdef FGMP_DBG_NOSTORE
+                if (row < M && col < N && acc[i][j][r] == 12345.678f) Y[row * ldy + col] = acc[i][j][r] * ss;
+#else
                 if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
+#endif
             }
         }
 }
+
+#ifndef FGMP_GEMM_WM
+#define FGMP_GEMM_WM 2
+#define FGMP_GEMM_WN 4
+#endif
 
 static inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
@@ -248,7 +311,8 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
                        w.Mp / kTileRows);
     hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((db + 3) / 4)), dim3(256), 0, st, B, lb, b16, w.ld,
                        w.Np / kTileRows);
-    hipLaunchKernelGGL(gemm_f16_kernel, dim3((unsigned)(n_tm * n_tn)), dim3(256), 0, st, a16, b16, w.ld,
+    hipLaunchKernelGGL((gemm_f16_kernel<FGMP_GEMM_WM, FGMP_GEMM_WN>), dim3((unsigned)(n_tm * n_tn)),
+                       dim3(FGMP_GEMM_WM * FGMP_GEMM_WN * 64), 0, st, a16, b16, w.ld,
                        (int)(w.ld / kBK), Y, ldy, M, N, n_tm, n_tn, A.hdr, B.hdr);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }

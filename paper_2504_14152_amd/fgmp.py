@@ -33,8 +33,10 @@ def lib() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.lib_path()
+    path = os.environ.get("FGMP_LIB_PATH") or _build.lib_path()   # override: a library built elsewhere
     if not os.path.exists(path):
+        if path != _build.lib_path():
+            raise FgmpError(f"FGMP_LIB_PATH={path} does not exist")
         _build.build()
     L = ctypes.CDLL(path)
     vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
