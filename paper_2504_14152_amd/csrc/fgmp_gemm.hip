@@ -280,7 +280,20 @@ static GemmWorkspace gemm_ws_layout(int64_t M, int64_t N, int64_t K)
     return w;
 }
 
-size_t gemm_only_workspace_bytes(int64_t M, int64_t N, int64_t K) { return gemm_ws_layout(M, N, K).total; }
+constexpr int64_t kSkinnyMaxM = 32;   // at most this many rows of X take the weight-streaming path
+
+size_t gemm_only_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    return M <= kSkinnyMaxM ? gemm_skinny_workspace_bytes(M, N, K) : gemm_ws_layout(M, N, K).total;
+}
+
+void launch_decode_f16(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad,
+                       hipStream_t st)
+{
+    const int64_t waves = n_rt_pad * l.n_kt;
+    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, v, l, out, ld,
+                       n_rt_pad);
+}
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
@@ -296,21 +309,20 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
     if (K % kBlock != 0 || ldy < N) return FGMP_ERR_BAD_SHAPE;
     if (((uintptr_t)packed_X | (uintptr_t)packed_W | (uintptr_t)Y | (uintptr_t)workspace) % 16 != 0)
         return FGMP_ERR_BAD_ALIGN;
-    const GemmWorkspace w = gemm_ws_layout(M, N, K);
-    if (workspace_bytes < w.total) return FGMP_ERR_BUFFER_TOO_SMALL;
+    if (workspace_bytes < gemm_only_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
     const PackedLayout la = make_layout(M, K), lb = make_layout(N, K);
     const PackedView A = make_view(const_cast<void *>(packed_X), la);
     const PackedView B = make_view(const_cast<void *>(packed_W), lb);
+    if (M <= kSkinnyMaxM) return gemm_skinny(A, la, B, lb, M, N, K, Y, ldy, workspace, st);
+    const GemmWorkspace w = gemm_ws_layout(M, N, K);
     _Float16 *a16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
     _Float16 *b16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_b);
     const int64_t n_tm = w.Mp / kBM, n_tn = w.Np / kBN;
     const int64_t da = (w.Mp / kTileRows) * la.n_kt, db = (w.Np / kTileRows) * lb.n_kt;
     if (n_tm * n_tn > 0x7FFFFFFF || (da + 3) / 4 > 0x7FFFFFFF || (db + 3) / 4 > 0x7FFFFFFF)
         return FGMP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((da + 3) / 4)), dim3(256), 0, st, A, la, a16, w.ld,
-                       w.Mp / kTileRows);
-    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((db + 3) / 4)), dim3(256), 0, st, B, lb, b16, w.ld,
-                       w.Np / kTileRows);
+    launch_decode_f16(A, la, a16, w.ld, w.Mp / kTileRows, st);
+    launch_decode_f16(B, lb, b16, w.ld, w.Np / kTileRows, st);
     hipLaunchKernelGGL((gemm_f16_kernel<FGMP_GEMM_WM, FGMP_GEMM_WN>), dim3((unsigned)(n_tm * n_tn)),
                        dim3(FGMP_GEMM_WM * FGMP_GEMM_WN * 64), 0, st, a16, b16, w.ld,
                        (int)(w.ld / kBK), Y, ldy, M, N, n_tm, n_tn, A.hdr, B.hdr);

@@ -26,6 +26,11 @@ fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
                           float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K);
+fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
+                          int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st);
+void launch_decode_f16(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad,
+                       hipStream_t st);
 fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);

@@ -288,11 +288,18 @@ def test_gemm_fc2_shape_sampled():
     _check_gemm(c, Y, rows, cols, label="fc2 sampled")
 
 
-@pytest.mark.parametrize("M", [1, 8, 32])
-def test_gemm_decode_shapes(M):
-    K, N = 4096, 4096
-    _say(f"gemm decode M={M}")
-    c = _quantized_pair(M, K, N, 11, 0.1, per_elem_w=False)
+@pytest.mark.parametrize("M,K,N,p", [(1, 4096, 4096, 0.1), (8, 4096, 4096, 0.1), (32, 4096, 4096, 0.1),
+                                     (17, 11008, 4096, 0.1), (5, 304, 100, 0.3), (32, 1024, 72, 1.0),
+                                     (16, 2048, 264, 0.5), (3, 4096, 12288, 0.0)])
+def test_gemm_decode_shapes(M, K, N, p):
+    """Weight-streaming path (M <= 32): K ranges combined in K order, ragged N and
+    K, and FP8 fractions beyond the speculative plane-H window."""
+    _say(f"gemm decode M={M} K={K} N={N} p={p}")
+    c = _quantized_pair(M, K, N, 11, p, per_elem_w=False)
     Y = fgmp.gemm(c["pX"], c["pW"])
-    cols = np.arange(0, N, 7)
-    _check_gemm(c, Y, np.arange(M), cols, label=f"decode M={M}")
+    cols = np.arange(0, N, 7) if N > 1000 else np.arange(N)
+    _check_gemm(c, Y, np.arange(M), cols, label=f"decode M={M} K={K} N={N} p={p}")
+    Y2 = fgmp.gemm(c["pX"], c["pW"])
+    assert torch.equal(Y, Y2), "split-K combination must be deterministic"
+    Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    assert torch.equal(Y, Yf)
