@@ -29,21 +29,6 @@ __device__ __forceinline__ void load16(const float *src, float (&x)[16])
     }
 }
 
-__device__ __forceinline__ void load16(const uint16_t *src, float (&x)[16])
-{
-    const uint4 *p = reinterpret_cast<const uint4 *>(src);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        uint4 v = p[i];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {   // bf16 -> fp32 is a 16-bit shift
-            x[8 * i + 2 * j + 0] = u2f(w[j] << 16);
-            x[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
-        }
-    }
-}
-
 struct QuantParams {
     const void *X;
     int64_t ldx, rows, nb;
@@ -59,10 +44,71 @@ struct QuantParams {
 
 enum { kModeStrided = 0, kModeCount = 1, kModeCompact = 2 };
 
+// Raw (unconverted) 16 input elements of one block: 2 x 16 B of bf16 or 4 x 16 B of fp32.
+template <typename Tin> struct RawBlock;
+template <> struct RawBlock<uint16_t> { uint4 v[2]; };
+template <> struct RawBlock<float> { uint4 v[4]; };
+
+template <typename Tin> __device__ __forceinline__ void load_raw(const Tin *src, RawBlock<Tin> &r)
+{
+    const uint4 *p = reinterpret_cast<const uint4 *>(src);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(r.v) / sizeof(uint4)); ++i) r.v[i] = p[i];
+}
+
+__device__ __forceinline__ void widen(const RawBlock<uint16_t> &r, float (&x)[16])
+{
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t w[4] = {r.v[i].x, r.v[i].y, r.v[i].z, r.v[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {   // bf16 -> fp32 is a 16-bit shift
+            x[8 * i + 2 * j + 0] = u2f(w[j] << 16);
+            x[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+        }
+    }
+}
+
+__device__ __forceinline__ void widen(const RawBlock<float> &r, float (&x)[16])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[4 * i + 0] = u2f(r.v[i].x); x[4 * i + 1] = u2f(r.v[i].y);
+        x[4 * i + 2] = u2f(r.v[i].z); x[4 * i + 3] = u2f(r.v[i].w);
+    }
+}
+
+// FP8 codes of 16 values (already multiplied by 1/S) as four dwords.
+template <bool kHW, bool kClamp> __device__ __forceinline__ void encode_fp8_block(const float (&r)[16], uint32_t (&c)[4])
+{
+    if constexpr (kHW) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            short2_t acc = {0, 0};
+            float a0 = r[4 * j], a1 = r[4 * j + 1], a2 = r[4 * j + 2], a3 = r[4 * j + 3];
+            if constexpr (kClamp) {   // the instruction returns NaN instead of saturating beyond 464
+                a0 = __builtin_amdgcn_fmed3f(a0, -448.0f, 448.0f);
+                a1 = __builtin_amdgcn_fmed3f(a1, -448.0f, 448.0f);
+                a2 = __builtin_amdgcn_fmed3f(a2, -448.0f, 448.0f);
+                a3 = __builtin_amdgcn_fmed3f(a3, -448.0f, 448.0f);
+            }
+            acc = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(acc, a0, a1, 1.0f, false);
+            acc = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(acc, a2, a3, 1.0f, true);
+            c[j] = (uint32_t)(uint16_t)acc[0] | ((uint32_t)(uint16_t)acc[1] << 16);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            c[j] = e4m3_encode_int(r[4 * j]) | (e4m3_encode_int(r[4 * j + 1]) << 8) |
+                   (e4m3_encode_int(r[4 * j + 2]) << 16) | (e4m3_encode_int(r[4 * j + 3]) << 24);
+    }
+}
+
 // grid.x = K-tiles, grid.y = groups of 4 * rt_per_wave row-tiles; 4 waves per
 // workgroup work on 4 adjacent row-tiles of the same K-tile at a time, so the
-// per-channel sensitivities stay in registers across the loop.
-template <typename Tin, bool kPerElem, bool kHW>
+// per-channel sensitivities stay in registers across the loop.  The input of
+// the next row-tile is fetched while the current one is processed.
+template <typename Tin, bool kPerElem, bool kHW, int kMode>
 __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -84,21 +130,32 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
     const float inv_S = 1.0f / p.S;
     const float S6 = 6.0f * p.S;
 
-    for (int it = 0; it < p.rt_per_wave; ++it) {
-        const int64_t rt = ((int64_t)blockIdx.y * p.rt_per_wave + it) * 4 + wave;
-        if (rt >= p.n_rt) break;
+    const int64_t rt0 = (int64_t)blockIdx.y * p.rt_per_wave * 4 + wave;
+    // out-of-range lanes read a valid address (their own K-tile's first block of row 0) and are masked
+    auto src_of = [&](int64_t rt) -> const Tin * {
+        const int64_t row = rt * kTileRows + rloc;
+        const bool ok = kvalid && row < p.rows;
+        return X + (ok ? row * p.ldx + kb * kBlock : 0);
+    };
+    if (rt0 >= p.n_rt) return;
+    const int64_t left = (p.n_rt - rt0 + 3) / 4;
+    const int n_it = (int)(left < p.rt_per_wave ? left : p.rt_per_wave);
+
+    auto process = [&](int64_t rt, const RawBlock<Tin> &raw_in) {
         const int64_t row = rt * kTileRows + rloc;
         const bool valid = kvalid && row < p.rows;
 
         float x[16];
-        if (valid) {
-            load16(X + row * p.ldx + kb * kBlock, x);
-            if constexpr (kPerElem) load16(p.fisher + row * p.ld_fisher + kb * kBlock, f);
-        } else {
+        widen(raw_in, x);
+        if (!valid) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                x[i] = 0.0f;
-                if constexpr (kPerElem) f[i] = 0.0f;
+            for (int i = 0; i < 16; ++i) x[i] = 0.0f;
+        }
+        if constexpr (kPerElem) {
+            if (valid) load16(p.fisher + row * p.ld_fisher + kb * kBlock, f);
+            else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) f[i] = 0.0f;
             }
         }
 
@@ -112,29 +169,32 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
         const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
 
         // NVFP4 codes, reconstruction, weighted squared error
-        uint32_t q_lo = 0, q_hi = 0;
+        uint32_t q[2] = {0u, 0u};
         float t[16];
+        if constexpr (kHW) {
+            // each conversion fills one byte of the code word in place (the byte selector is an immediate)
+#define FGMP_ENC(W, B, I) q[W] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q[W], x[I] * inv_d, x[I + 1] * inv_d, 1.0f, B)
+            FGMP_ENC(0, 0, 0); FGMP_ENC(0, 1, 2); FGMP_ENC(0, 2, 4); FGMP_ENC(0, 3, 6);
+            FGMP_ENC(1, 0, 8); FGMP_ENC(1, 1, 10); FGMP_ENC(1, 2, 12); FGMP_ENC(1, 3, 14);
+#undef FGMP_ENC
+#define FGMP_ERR(W, B, I)                                                                          \
+    {                                                                                              \
+        const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);                \
+        const float e0 = x[I] - v[0] * d, e1 = x[I + 1] - v[1] * d;                                \
+        t[I] = (e0 * e0) * f[I];                                                                   \
+        t[I + 1] = (e1 * e1) * f[I + 1];                                                           \
+    }
+            FGMP_ERR(0, 0, 0) FGMP_ERR(0, 1, 2) FGMP_ERR(0, 2, 4) FGMP_ERR(0, 3, 6)
+            FGMP_ERR(1, 0, 8) FGMP_ERR(1, 1, 10) FGMP_ERR(1, 2, 12) FGMP_ERR(1, 3, 14)
+#undef FGMP_ERR
+        } else {
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-            const float r0 = x[i] * inv_d, r1 = x[i + 1] * inv_d;
-            uint32_t byte;
-            float v0, v1;
-            if constexpr (kHW) {
-                byte = e2m1_encode_pair_hw(r0, r1);
-                float2_t v = e2m1_decode_pair_hw(byte);
-                v0 = v[0];
-                v1 = v[1];
-            } else {
-                const uint32_t c0 = e2m1_encode_int(r0), c1 = e2m1_encode_int(r1);
-                byte = c0 | (c1 << 4);
-                v0 = e2m1_decode_int(c0);
-                v1 = e2m1_decode_int(c1);
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t c = e2m1_encode_int(x[i] * inv_d);
+                q[i >> 3] |= c << (4 * (i & 7));
+                const float e = x[i] - e2m1_decode_int(c) * d;
+                t[i] = (e * e) * f[i];
             }
-            if (i < 8) q_lo |= byte << (4 * i);
-            else q_hi |= byte << (4 * (i - 8));
-            const float e0 = x[i] - v0 * d, e1 = x[i + 1] - v1 * d;
-            t[i] = (e0 * e0) * f[i];
-            t[i + 1] = (e1 * e1) * f[i + 1];
         }
 #pragma unroll
         for (int w = 16; w > 1; w >>= 1)
@@ -147,42 +207,50 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
         const int64_t tile = rt * p.n_kt + kt;
         if (p.scores != nullptr && valid) p.scores[row * p.nb + kb] = score;
 
-        if (p.mode == kModeCount) {
+        if constexpr (kMode == kModeCount) {
             if (lane == 0) p.out.T[tile] = (uint32_t)__popcll(ballot);
-            continue;
-        }
-
-        const uint32_t prefix = (uint32_t)__popcll(ballot & ((1ull << lane) - 1ull));
-        uint32_t hbase;
-        if (p.mode == kModeStrided) {
-            hbase = (uint32_t)(tile * kTileSlots);
-            if (lane == 0) p.out.T[tile] = hbase;
         } else {
-            hbase = p.out.T[tile];
-        }
-        if (lane == 0) p.out.M[tile] = ballot;
-
-        uint2 lword = make_uint2(q_lo, q_hi);
-        uint32_t sbyte = sc;
-        if (ballot != 0ull) {
-            if (hi) {
-                uint32_t c[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float r0 = x[i] * inv_S, r1 = x[i + 1] * inv_S;
-                    uint32_t two;
-                    if constexpr (kHW) two = e4m3_encode_pair_hw(r0, r1);
-                    else two = e4m3_encode_int(r0) | (e4m3_encode_int(r1) << 8);
-                    c[i / 4] |= two << (8 * (i & 3));
-                }
-                lword = make_uint2(c[0], c[1]);
-                p.out.H[(uint64_t)hbase + prefix] = make_uint2(c[2], c[3]);
-                sbyte = prefix;
+            const uint32_t prefix = (uint32_t)__popcll(ballot & ((1ull << lane) - 1ull));
+            uint32_t hbase;
+            if constexpr (kMode == kModeStrided) {
+                hbase = (uint32_t)(tile * kTileSlots);
+                if (lane == 0) p.out.T[tile] = hbase;
+            } else {
+                hbase = p.out.T[tile];
             }
+            if (lane == 0) p.out.M[tile] = ballot;
+
+            uint2 lword = make_uint2(q[0], q[1]);
+            uint32_t sbyte = sc;
+            if (ballot != 0ull) {
+                // values beyond the FP8 range only occur when the caller's S is below amax / 448
+                const bool any_big = __ballot(hi && amax * inv_S > 448.0f) != 0ull;
+                if (hi) {
+                    float r[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                    uint32_t c[4];
+                    if (any_big) encode_fp8_block<kHW, true>(r, c);
+                    else encode_fp8_block<kHW, false>(r, c);
+                    lword = make_uint2(c[0], c[1]);
+                    p.out.H[(uint64_t)hbase + prefix] = make_uint2(c[2], c[3]);
+                    sbyte = prefix;
+                }
+            }
+            p.out.L[tile * kTileSlots + lane] = lword;
+            p.out.S[tile * kTileSlots + lane] = (uint8_t)sbyte;
         }
-        p.out.L[tile * kTileSlots + lane] = lword;
-        p.out.S[tile * kTileSlots + lane] = (uint8_t)sbyte;
+    };
+
+    // software pipeline: the next row-tile's input is in flight while this one is processed
+    RawBlock<Tin> cur, nxt;
+    load_raw(src_of(rt0), cur);
+    for (int it = 0; it + 1 < n_it; ++it) {
+        load_raw(src_of(rt0 + 4 * (int64_t)(it + 1)), nxt);
+        process(rt0 + 4 * (int64_t)it, cur);
+        cur = nxt;
     }
+    process(rt0 + 4 * (int64_t)(n_it - 1), cur);
 }
 
 // Exclusive prefix sum over the per-tile FP8 counts in plane T (one workgroup),
@@ -272,19 +340,32 @@ __global__ __launch_bounds__(256) void unpack_kernel(PackedView v, PackedLayout 
 
 static int pick_rt_per_wave(int64_t n_rt)
 {
+#ifdef FGMP_DBG_RTPW
+    if (const char *e = getenv("FGMP_RTPW")) return atoi(e);
+#endif
     // enough work per wave to amortize the sensitivity loads, enough workgroups to fill 256 CUs
     if (n_rt >= 4096) return 4;
     if (n_rt >= 1024) return 2;
     return 1;
 }
 
+template <typename Tin, int kMode>
+static void launch_quantize_mode(const QuantParams &p, bool per_elem, dim3 grid, hipStream_t st)
+{
+    if (per_elem)
+        hipLaunchKernelGGL((quantize_kernel<Tin, true, kUseHwCvt, kMode>), grid, dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((quantize_kernel<Tin, false, kUseHwCvt, kMode>), grid, dim3(256), 0, st, p);
+}
+
 template <typename Tin>
 static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipStream_t st)
 {
-    if (per_elem)
-        hipLaunchKernelGGL((quantize_kernel<Tin, true, kUseHwCvt>), grid, dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL((quantize_kernel<Tin, false, kUseHwCvt>), grid, dim3(256), 0, st, p);
+    switch (p.mode) {
+    case kModeStrided: launch_quantize_mode<Tin, kModeStrided>(p, per_elem, grid, st); break;
+    case kModeCount: launch_quantize_mode<Tin, kModeCount>(p, per_elem, grid, st); break;
+    default: launch_quantize_mode<Tin, kModeCompact>(p, per_elem, grid, st); break;
+    }
 }
 
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
