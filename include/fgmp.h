@@ -138,6 +138,17 @@ fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K,
                                     uint8_t *scales, uint8_t *mask, void *stream);
 
 /*
+ * Decode a packed tensor to dense FP16 (IEEE binary16), the operand form the
+ * GEMM kernels multiply: FP8 block -> its E4M3 values; FP4 block -> E2M1 value
+ * times the E4M3 block scale (exact in FP16); the tensor scale is not applied.
+ *   out   rows_out x ld halves, rows_out >= rows a multiple of 8, ld >= K
+ *         rounded up to a multiple of 128 exactly; rows and columns beyond the tensor
+ *         are written as zeros
+ */
+fgmp_status_t fgmp_dequantize_f16(const void *packed, int64_t rows, int64_t K, void *out, int64_t rows_out,
+                                  int64_t ld, void *stream);
+
+/*
  * Offline helpers.  These synchronize `stream` and use host memory.
  */
 

@@ -73,6 +73,21 @@ fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K,
     return unpack_tensor(packed, rows, K, codes, scales, mask, as_stream(stream));
 }
 
+fgmp_status_t fgmp_dequantize_f16(const void *packed, int64_t rows, int64_t K, void *out, int64_t rows_out,
+                                  int64_t ld, void *stream)
+{
+    if (!packed || !out || rows <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    const PackedLayout l = make_layout(rows, K);
+    if (rows_out < rows || rows_out % kTileRows != 0 || ld != l.n_kt * kTileK) return FGMP_ERR_BAD_SHAPE;
+    if (((uintptr_t)packed | (uintptr_t)out) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
+    const DecodeJob job = make_decode_job(make_view(const_cast<void *>(packed), l), l, static_cast<_Float16 *>(out),
+                                          ld, rows_out / kTileRows);
+    const fgmp_status_t rc = launch_decode_f16(job, nullptr, nullptr, 0, as_stream(stream));
+    if (rc != FGMP_OK) return rc;
+    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
 fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host, void *stream)
 {
     if (!packed || !info_host) return FGMP_ERR_INVALID_ARG;

@@ -53,28 +53,62 @@ __device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, i
     }
 }
 
-// One wave per 8 x 128 tile of the zero-padded FP16 matrix out[rows_pad][ld].
-__global__ __launch_bounds__(256) void decode_f16_kernel(PackedView v, PackedLayout l, _Float16 *out, int64_t ld,
-                                                          int64_t n_rt_pad)
+// One wave per 8 x 128 tile of the zero-padded FP16 matrix out[8 n_rt_pad][ld].
+// One launch serves up to two tensors (both GEMM operands) and can clear a
+// small array of counters on the side.
+__global__ __launch_bounds__(256) void decode_f16_kernel(DecodeJob ja, DecodeJob jb, uint32_t *zero, int64_t zero_n)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (id >= n_rt_pad * l.n_kt) return;
+    int64_t id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    {
+        const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (gid < zero_n) zero[gid] = 0u;
+    }
+    const bool second = id >= ja.waves;
+    if (second) id -= ja.waves;
+    const DecodeJob &j = second ? jb : ja;
+    if (id >= j.waves) return;
+    const PackedLayout &l = j.l;
     const int64_t rt = id / l.n_kt, kt = id % l.n_kt;
     half2_t vals[8];
     // an operand whose header does not describe the shape this launch assumes decodes to zeros
-    const bool header_ok = v.hdr->magic == kMagic && v.hdr->rows == l.rows && v.hdr->K == l.K;
+    const bool header_ok = j.v.hdr->magic == kMagic && j.v.hdr->rows == l.rows && j.v.hdr->K == l.K;
     if (rt < l.n_rt && header_ok) {
-        decode_slot(v, rt * l.n_kt + kt, lane, vals);
+        decode_slot(j.v, rt * l.n_kt + kt, lane, vals);
     } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vals[j] = half2_t{(_Float16)0.0f, (_Float16)0.0f};
+        for (int i = 0; i < 8; ++i) vals[i] = half2_t{(_Float16)0.0f, (_Float16)0.0f};
     }
-    _Float16 *dst = out + (rt * kTileRows + (lane >> 3)) * ld + kt * kTileK + (lane & 7) * kBlock;
+    _Float16 *dst = j.out + (rt * kTileRows + (lane >> 3)) * j.ld + kt * kTileK + (lane & 7) * kBlock;
     uint4 *d4 = reinterpret_cast<uint4 *>(dst);
     const uint32_t *w = reinterpret_cast<const uint32_t *>(vals);
     d4[0] = make_uint4(w[0], w[1], w[2], w[3]);
     d4[1] = make_uint4(w[4], w[5], w[6], w[7]);
+}
+
+DecodeJob make_decode_job(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad)
+{
+    DecodeJob j;
+    j.v = v;
+    j.l = l;
+    j.out = out;
+    j.ld = ld;
+    j.waves = n_rt_pad * l.n_kt;
+    return j;
+}
+
+fgmp_status_t launch_decode_f16(const DecodeJob &a, const DecodeJob *b, uint32_t *zero, int64_t zero_n,
+                                hipStream_t st)
+{
+    DecodeJob none = a;
+    none.waves = 0;
+    const DecodeJob &jb = b ? *b : none;
+    int64_t blocks = (a.waves + jb.waves + 3) / 4;
+    const int64_t zblocks = (zero_n + 255) / 256;
+    if (blocks < zblocks) blocks = zblocks;
+    if (blocks > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a, jb, zero, zero_n);
+    return FGMP_OK;
 }
 
 // ---------------------------------------------------------------------------
@@ -287,14 +321,6 @@ size_t gemm_only_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return M <= kSkinnyMaxM ? gemm_skinny_workspace_bytes(M, N, K) : gemm_ws_layout(M, N, K).total;
 }
 
-void launch_decode_f16(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad,
-                       hipStream_t st)
-{
-    const int64_t waves = n_rt_pad * l.n_kt;
-    hipLaunchKernelGGL(decode_f16_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, v, l, out, ld,
-                       n_rt_pad);
-}
-
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     // the fused call also keeps the packed activations here
@@ -318,11 +344,11 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
     _Float16 *a16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
     _Float16 *b16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_b);
     const int64_t n_tm = w.Mp / kBM, n_tn = w.Np / kBN;
-    const int64_t da = (w.Mp / kTileRows) * la.n_kt, db = (w.Np / kTileRows) * lb.n_kt;
-    if (n_tm * n_tn > 0x7FFFFFFF || (da + 3) / 4 > 0x7FFFFFFF || (db + 3) / 4 > 0x7FFFFFFF)
-        return FGMP_ERR_UNSUPPORTED;
-    launch_decode_f16(A, la, a16, w.ld, w.Mp / kTileRows, st);
-    launch_decode_f16(B, lb, b16, w.ld, w.Np / kTileRows, st);
+    if (n_tm * n_tn > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
+    const DecodeJob ja = make_decode_job(A, la, a16, w.ld, w.Mp / kTileRows);
+    const DecodeJob jb = make_decode_job(B, lb, b16, w.ld, w.Np / kTileRows);
+    const fgmp_status_t rc = launch_decode_f16(ja, &jb, nullptr, 0, st);
+    if (rc != FGMP_OK) return rc;
     hipLaunchKernelGGL((gemm_f16_kernel<FGMP_GEMM_WM, FGMP_GEMM_WN>), dim3((unsigned)(n_tm * n_tn)),
                        dim3(FGMP_GEMM_WM * FGMP_GEMM_WN * 64), 0, st, a16, b16, w.ld,
                        (int)(w.ld / kBK), Y, ldy, M, N, n_tm, n_tn, A.hdr, B.hdr);

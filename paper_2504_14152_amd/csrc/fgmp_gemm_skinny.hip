@@ -284,12 +284,6 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
 
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return skinny_plan(M, N, K).total; }
 
-__global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t *p, int64_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0u;
-}
-
 fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
                           int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st)
 {
@@ -300,10 +294,10 @@ fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const Pac
     uint32_t *counters = reinterpret_cast<uint32_t *>(ws + p.off_counters);
     if (p.row_groups * p.ksplit > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
     const int64_t n_rt_pad = (16 * p.mt) / kTileRows;
-    launch_decode_f16(X, lx, xh, p.ldx, n_rt_pad, st);
-    if (p.ksplit > 1)
-        hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((p.row_groups + 255) / 256)), dim3(256), 0, st,
-                           counters, p.row_groups);
+    // one launch decodes the activations and clears the arrival counters
+    const DecodeJob jx = make_decode_job(X, lx, xh, p.ldx, n_rt_pad);
+    const fgmp_status_t rc = launch_decode_f16(jx, nullptr, counters, p.ksplit > 1 ? p.row_groups : 0, st);
+    if (rc != FGMP_OK) return rc;
     const dim3 grid((unsigned)(p.row_groups * p.ksplit));
     if (p.mt == 1)
         hipLaunchKernelGGL((gemm_skinny_kernel<1>), grid, dim3(256), 0, st, W, lw, xh, p.ldx, p.cols_per_wg,

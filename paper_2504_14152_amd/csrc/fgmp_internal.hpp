@@ -29,8 +29,17 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K);
 fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
                           int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st);
-void launch_decode_f16(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad,
-                       hipStream_t st);
+// packed -> zero-padded dense FP16 [8 n_rt_pad][ld]; one launch decodes one or two tensors and
+// can clear `zero_n` 32-bit counters
+struct DecodeJob {
+    PackedView v;
+    PackedLayout l;
+    _Float16 *out;
+    int64_t ld, waves;
+};
+DecodeJob make_decode_job(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad);
+fgmp_status_t launch_decode_f16(const DecodeJob &a, const DecodeJob *b, uint32_t *zero, int64_t zero_n,
+                                hipStream_t st);
 fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);

@@ -40,9 +40,28 @@ struct QuantParams {
     float *scores;
     int mode;          // kModeStrided / kModeCount / kModeCompact
     int rt_per_wave;
+    PackedLayout layout;   // for the header, written by the first launch of a call
+    uint32_t compact;
 };
 
 enum { kModeStrided = 0, kModeCount = 1, kModeCompact = 2 };
+
+__device__ __forceinline__ void write_header(PackedHeader *hdr, const PackedLayout &l, float S, uint32_t compact)
+{
+    hdr->magic = kMagic;
+    hdr->version = kVersion;
+    hdr->rows = l.rows;
+    hdr->K = l.K;
+    hdr->tensor_scale = S;
+    hdr->compact = compact;
+    hdr->off_L = l.off_L;
+    hdr->off_S = l.off_S;
+    hdr->off_M = l.off_M;
+    hdr->off_T = l.off_T;
+    hdr->off_H = l.off_H;
+    hdr->h_entries = (uint64_t)l.n_tiles * kTileSlots;   // a compact tensor's scan overwrites these two
+    hdr->bytes_used = l.total_bytes;
+}
 
 // Raw (unconverted) 16 input elements of one block: 2 x 16 B of bf16 or 4 x 16 B of fp32.
 template <typename Tin> struct RawBlock;
@@ -129,6 +148,10 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
     }
     const float inv_S = 1.0f / p.S;
     const float S6 = 6.0f * p.S;
+    if constexpr (kMode != kModeCompact) {
+        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+            write_header(p.out.hdr, p.layout, p.S, p.compact);
+    }
 
     const int64_t rt0 = (int64_t)blockIdx.y * p.rt_per_wave * 4 + wave;
     // out-of-range lanes read a valid address (their own K-tile's first block of row 0) and are masked
@@ -284,24 +307,6 @@ __global__ __launch_bounds__(1024) void scan_tiles_kernel(uint32_t *T, int64_t n
     }
 }
 
-__global__ void write_header_kernel(PackedHeader *hdr, PackedLayout l, float S, uint32_t compact)
-{
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    hdr->magic = kMagic;
-    hdr->version = kVersion;
-    hdr->rows = l.rows;
-    hdr->K = l.K;
-    hdr->tensor_scale = S;
-    hdr->compact = compact;
-    hdr->off_L = l.off_L;
-    hdr->off_S = l.off_S;
-    hdr->off_M = l.off_M;
-    hdr->off_T = l.off_T;
-    hdr->off_H = l.off_H;
-    hdr->h_entries = (uint64_t)l.n_tiles * kTileSlots;
-    hdr->bytes_used = l.total_bytes;
-}
-
 // One wave per tile, one slot per lane: packed -> canonical arrays.
 __global__ __launch_bounds__(256) void unpack_kernel(PackedView v, PackedLayout l, uint8_t *codes,
                                                       uint8_t *scales, uint8_t *mask)
@@ -399,7 +404,8 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
     const dim3 grid((unsigned)l.n_kt, (unsigned)gy);
     const bool per_elem = ld_fisher != 0;
 
-    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, st, p.out.hdr, l, S, compact ? 1u : 0u);
+    p.layout = l;
+    p.compact = compact ? 1u : 0u;
     if (!compact) {
         p.mode = kModeStrided;
         if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
                                         vp, sz, vp]
     L.fgmp_unpack_canonical.restype = ctypes.c_int
     L.fgmp_unpack_canonical.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    L.fgmp_dequantize_f16.restype = ctypes.c_int
+    L.fgmp_dequantize_f16.argtypes = [vp, i64, i64, vp, i64, i64, vp]
     L.fgmp_packed_info.restype = ctypes.c_int
     L.fgmp_packed_info.argtypes = [vp, ctypes.POINTER(_PackedInfo), vp]
     L.fgmp_threshold_for_fraction.restype = ctypes.c_int
@@ -190,6 +192,16 @@ def unpack_canonical(p: Packed):
     rc = lib().fgmp_unpack_canonical(_ptr(p.buf), p.rows, p.K, _ptr(codes), _ptr(scales), _ptr(mask), _stream())
     _check(rc, "fgmp_unpack_canonical")
     return codes, scales, mask
+
+
+def dequantize_f16(p: Packed, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Dense FP16 values (without the tensor scale), zero-padded to [rows_out, ld]."""
+    ld = -(-p.K // 128) * 128
+    if out is None:
+        out = torch.empty((-(-p.rows // 8) * 8, ld), dtype=torch.float16, device=p.buf.device)
+    rc = lib().fgmp_dequantize_f16(_ptr(p.buf), p.rows, p.K, _ptr(out), out.shape[0], out.stride(0), _stream())
+    _check(rc, "fgmp_dequantize_f16")
+    return out
 
 
 def packed_info(p: Packed) -> dict:

@@ -39,7 +39,7 @@ def test_sizes_and_host_side_argument_checks():
     L = fgmp.lib()
     assert L.fgmp_quantize_activations(None, 0, 8, 128, 128, None, 0.0, 1.0, None, 0, None, None) == -1
     assert L.fgmp_gemm(None, 1, None, 1, 16, None, 1, None, 0, None) == -1
-    assert L.fgmp_gemm(256, 1, 256, 1, 24, 256, 1, None, 0, None) == -2
+    assert L.fgmp_gemm(256, 1, 256, 1, 24, 256, 1, 256, 0, None) == -2
     assert L.fgmp_unpack_canonical(None, 1, 16, None, None, None, None) == -1
 
 

@@ -166,6 +166,21 @@ def test_quantize_weights(N, K, bf16, per_elem, p):
     assert algorithmic <= info["bytes_used"] <= tiles * 64 * 9 + n_hi * 8 + tiles * 12 + 6 * 256
 
 
+@pytest.mark.parametrize("rows,K,p", [(13, 304, 0.3), (256, 4096, 0.1), (64, 1024, 1.0), (40, 256, 0.0)])
+def test_dequantize_f16_is_exact(rows, K, p):
+    """The FP16 operand form equals the oracle's real-valued decode bit for bit."""
+    x = synth.activations(rows, K, 8, 61, outlier_count=3)
+    f = synth.fisher_per_channel(K, 8, 62)
+    S = float(synth.default_tensor_scale(x))
+    T = orc.threshold(orc.quantize(x, f, np.inf, S)["scores"], p)
+    want = orc.quantize(x, f, T, S)
+    pk = fgmp.quantize_activations(torch.from_numpy(x).to(DEV), torch.from_numpy(f).to(DEV), T, S)
+    got = fgmp.dequantize_f16(pk).cpu().numpy()
+    ref = orc.dequantize(want["codes"], want["scales"], want["mask"])
+    assert np.array_equal(got[:rows, :K].astype(np.float64), ref)
+    assert not got[rows:].any() and not got[:, K:].any()
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)
