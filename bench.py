@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the FP8-fraction sweep at the Llama-2-70B FC1 shape (configs[4]; a few GB, ~1 min)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -220,6 +222,43 @@ def main() -> int:
                     "packed_w_bytes": used}
             del pool
         extra["decode_hbm_cold"] = dec
+    def prefill_case(Mp_, Kp_, Np_, p_w, p_x, kind, tid):
+        """Fused step on another prefill shape; returns ms and TFLOP/s (per-channel weight Fisher)."""
+        xp, xpb = dev_bf16(synth.activations(Mp_, Kp_, 0, tid, kind=kind))
+        sxp = float(synth.default_tensor_scale(synth.bf16_bits_to_f32(xpb)))
+        del xpb
+        wp = torch.empty((Np_, Kp_), dtype=torch.bfloat16, device=dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1000 + tid)
+        wp.normal_(0.0, 0.02, generator=gen)       # weights of this size are drawn on the device
+        swp = float(wp.abs().max().float()) / 448.0
+        fxp = torch.from_numpy(synth.fisher_per_channel(Kp_, 0, tid + 1)).to(dev)
+        fwp = torch.from_numpy(synth.fisher_per_channel(Kp_, 0, tid + 2)).to(dev)
+        _, sc_w = fgmp.quantize_weights(wp, fwp, float("inf"), swp, want_scores=True)
+        Twp = fgmp.threshold_for_fraction(sc_w, p_w)
+        del sc_w
+        pWp = fgmp.quantize_weights(wp, fwp, Twp, swp)
+        del wp
+        _, sc_x = fgmp.quantize_activations(xp, fxp, float("inf"), sxp, want_scores=True)
+        Txp = fgmp.threshold_for_fraction(sc_x, p_x)
+        del sc_x
+        Yp = torch.empty((Mp_, Np_), dtype=torch.float32, device=dev)
+        wsp = torch.empty(fgmp.workspace_bytes(Mp_, Np_, Kp_), dtype=torch.uint8, device=dev)
+        ms_p = timed(lambda: fgmp.quant_gemm_fused(xp, fxp, Txp, sxp, pWp, out=Yp, workspace=wsp), 10, 5)
+        info = fgmp.packed_info(pWp)
+        return {"ms_per_step": round(ms_p, 4), "TFLOPs": round(2.0 * Mp_ * Np_ * Kp_ / (ms_p * 1e-3) / 1e12, 1),
+                "frac_mfma_peak": round(2.0 * Mp_ * Np_ * Kp_ / (ms_p * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS, 4),
+                "fp8_fraction_w": round(info["n_fp8_blocks"] / info["n_blocks"], 4), "packed_w_bytes": info["bytes_used"]}
+
+    if not args.no_extra:
+        # MLP prefill shapes (configs[2]); whole fused step, activation quantization included
+        extra["prefill_fc1_4096x4096x22016"] = prefill_case(4096, 4096, 22016, P_FP8, P_FP8, "normal", 40)
+        extra["prefill_fc2_4096x11008x4096"] = prefill_case(4096, 11008, 4096, P_FP8, P_FP8, "silu_gate", 50)
+    if args.sweep:
+        sw_res = {}
+        for frac in (0.0, 0.1, 0.2, 0.3, 1.0):
+            sw_res[f"fp8_{int(frac * 100)}pct"] = prefill_case(2048, 8192, 57344, frac, frac, "normal", 60)
+        extra["sweep_llama2_70b_fc1_2048x8192x57344"] = sw_res
     out["extra"] = extra
 
     # ------------------------------------------------------------ CPU baseline: the oracle on a bounded sample

@@ -151,16 +151,16 @@ __device__ __forceinline__ void tile_coords(int64_t n_tm, int64_t n_tn, int64_t 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void global_void_t;
 
-// Scheduling hint for one pipeline phase: spread its kReads LDS reads (and
-// 2 * kVmem global->LDS loads) evenly between its kMfma MFMAs.
-template <int G, int kReads, int kMfma, int kVmem> __device__ __forceinline__ void interleave_phase()
+// Scheduling hint for one pipeline phase: first the 2 * kVmem global->LDS loads
+// and the kReads LDS reads that fetch the next phase's fragments, then the
+// kMfma MFMAs on the fragments read one phase earlier.  The reads then have a
+// whole phase of MFMA time to land, so no MFMA waits on a read just issued.
+template <int kReads, int kMfma, int kVmem> __device__ __forceinline__ void order_phase()
 {
-    if constexpr (G < kReads) {
-        if constexpr (G < kVmem) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, (kMfma * (G + 1)) / kReads - (kMfma * G) / kReads, 0);
-        interleave_phase<G + 1, kReads, kMfma, kVmem>();
-    }
+    if constexpr (kVmem > 0) __builtin_amdgcn_sched_group_barrier(0x020, 2 * kVmem, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, kMfma, 0);
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 // kWM x kWN waves per workgroup; each wave owns a (256 / kWM) x (256 / kWN)
@@ -199,8 +199,13 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
         for (int i = 0; i < kLoads; ++i) {
             __builtin_amdgcn_global_load_lds((global_void_t *)(ga + i * row_step + (int64_t)kt * kRowBytes),
                                              (lds_void_t *)&lds[stage][0][(kWaves * i + wave) * 1024], 16, 0, 0);
+#ifdef FGMP_DBG_BTHIRD
+            if (i % 3 == 0)
+#endif
+#ifndef FGMP_DBG_NOB
             __builtin_amdgcn_global_load_lds((global_void_t *)(gb + i * row_step + (int64_t)kt * kRowBytes),
                                              (lds_void_t *)&lds[stage][1][(kWaves * i + wave) * 1024], 16, 0, 0);
+#endif
         }
     };
 
@@ -219,11 +224,18 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
         frag_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
     auto read_frags = [&](int stage, int kk, half8_t (&a)[TM], half8_t (&b)[TN]) {
+#ifdef FGMP_DBG_NOLDSREAD
+        if (kk >= 0) return;
+#endif
         const char *la = &lds[stage][0][wm * (TM * 32) * kRowBytes], *lb = &lds[stage][1][wn * (TN * 32) * kRowBytes];
+#ifndef FGMP_DBG_NOAREAD
 #pragma unroll
         for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const half8_t *>(la + i * 32 * kRowBytes + frag_off[kk]);
+#endif
+#ifndef FGMP_DBG_NOBREAD
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const half8_t *>(lb + j * 32 * kRowBytes + frag_off[kk]);
+#endif
     };
     auto mfma_block = [&](const half8_t (&a)[TM], const half8_t (&b)[TN]) {
 #ifdef FGMP_DBG_NOMFMA
@@ -250,24 +262,30 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     read_frags(0, 0, fa[0], fb[0]);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): enter the loop with an empty LDS queue (see its end)
     for (int kt = 0; kt < nk; ++kt) {
         const int st = kt & 1;
         read_frags(st, 1, fa[1], fb[1]);
         mfma_block(fa[0], fb[0]);
-        interleave_phase<0, kReads, kMfma, 0>();
+        order_phase<kReads, kMfma, 0>();
         read_frags(st, 2, fa[0], fb[0]);
         mfma_block(fa[1], fb[1]);
-        interleave_phase<0, kReads, kMfma, 0>();
+        order_phase<kReads, kMfma, 0>();
         read_frags(st, 3, fa[1], fb[1]);
         mfma_block(fa[0], fb[0]);
-        interleave_phase<0, kReads, kMfma, 0>();
+        order_phase<kReads, kMfma, 0>();
+#ifndef FGMP_DBG_NOBARRIER
         __builtin_amdgcn_s_waitcnt(0);   // own LDS reads done, own global->LDS loads landed
         __syncthreads();
+#endif
         // the last two iterations reload the final K-step, which nobody reads again
         issue_loads(kt + 2 < nk ? kt + 2 : nk - 1, st);
         read_frags(st ^ 1, 0, fa[0], fb[0]);
         mfma_block(fa[1], fb[1]);
-        interleave_phase<0, kReads, kMfma, kLoads>();
+        order_phase<kReads, kMfma, kLoads>();
+        // the fragments for the next iteration were requested a phase ago; waiting for them here (LDS
+        // counter only) costs nothing and lets the next iteration start with a known-empty LDS queue
+        __builtin_amdgcn_s_waitcnt(0xC07F);
     }
     __builtin_amdgcn_s_waitcnt(0);
 
