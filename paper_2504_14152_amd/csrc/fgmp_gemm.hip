@@ -6,52 +6,16 @@
 // cores and accumulated in FP32, which is what the paper's four dot-product
 // units followed by the FP32 partial-sum adder compute.
 //
-// Prefill path: a decode pass expands both packed operands to FP16 in the
-// caller's workspace (HBM-bound, a few percent of the GEMM time at these
-// shapes), then a 256x256x64-tiled MFMA kernel multiplies them.
-#include "fgmp_internal.hpp"
+// Prefill path (M > 32): the activations are expanded to FP16 in the caller's
+// workspace by a decode pass (small), and the 256x256x64-tiled MFMA kernel of
+// fgmp_gemm_mixed.hip decodes the packed weights itself.  This file holds the
+// decode pass, the dispatch, and the alternative two-pass path in which both
+// operands are expanded first and a plain FP16 kernel multiplies them.
+#include <stdlib.h>
+
+#include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
-
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float16_t __attribute__((ext_vector_type(16)));
-
-constexpr int kNumXcd = 8;
-
-// ---------------------------------------------------------------------------
-// packed -> FP16 decode
-// ---------------------------------------------------------------------------
-
-// Decode the block in slot `lane` of `tile` to 16 FP16 values with the gfx950
-// conversion instructions (exact for every code; first element in the low
-// nibble / byte).
-__device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, int lane, half2_t (&out)[8])
-{
-    const uint2 lw = v.L[tile * kTileSlots + lane];
-    const uint32_t sb = v.S[tile * kTileSlots + lane];
-    const uint64_t mbits = v.M[tile];
-    if ((mbits >> lane) & 1ull) {
-        const uint2 hw = v.H[(uint64_t)v.T[tile] + sb];
-        out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.x, 1.0f, false);
-        out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.x, 1.0f, true);
-        out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.y, 1.0f, false);
-        out[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.y, 1.0f, true);
-        out[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.x, 1.0f, false);
-        out[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.x, 1.0f, true);
-        out[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.y, 1.0f, false);
-        out[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.y, 1.0f, true);
-    } else {
-        const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sb | (sb << 8), 1.0f, false);
-        out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 0) * s;
-        out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 1) * s;
-        out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 2) * s;
-        out[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 3) * s;
-        out[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 0) * s;
-        out[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 1) * s;
-        out[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 2) * s;
-        out[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 3) * s;
-    }
-}
 
 // One wave per 8 x 128 tile of the zero-padded FP16 matrix out[8 n_rt_pad][ld].
 // One launch serves up to two tensors (both GEMM operands) and can clear a
@@ -115,54 +79,6 @@ fgmp_status_t launch_decode_f16(const DecodeJob &a, const DecodeJob *b, uint32_t
 // dense FP16 x FP16 -> FP32 MFMA kernel, A [Mp][ld], B [Np][ld], both K-major
 // ---------------------------------------------------------------------------
 
-constexpr int kBM = 256, kBN = 256, kBK = 64;
-constexpr int kRowBytes = kBK * 2;               // 128 B of K per tile row, 8 chunks of 16 B
-constexpr int kTileBytes = kBM * kRowBytes;      // 32 KB per operand per stage
-
-// Map the hardware workgroup id (dispatched round-robin over the 8 XCDs) to a
-// logical tile id so that each XCD works on a contiguous range of tiles, then
-// to (tile_m, tile_n) in groups of 8 M-tiles so that concurrently running
-// workgroups share operand tiles in their XCD's L2.
-__device__ __forceinline__ void tile_coords(int64_t n_tm, int64_t n_tn, int64_t &tm, int64_t &tn)
-{
-    const int64_t n = n_tm * n_tn;
-    const int64_t id = blockIdx.x;
-    const int64_t xcd = id % kNumXcd, idx = id / kNumXcd;
-    const int64_t q = n / kNumXcd, rem = n % kNumXcd;
-    const int64_t logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
-    constexpr int64_t kGroup = 8;
-    const int64_t per_group = kGroup * n_tn;
-    const int64_t g = logical / per_group;
-    const int64_t first_m = g * kGroup;
-    const int64_t gsz = (n_tm - first_m < kGroup) ? n_tm - first_m : kGroup;
-    const int64_t in_g = logical % per_group;
-    tm = first_m + in_g % gsz;
-    tn = in_g / gsz;
-}
-
-// LDS tile layout: row r of a 256 x 64 operand tile occupies 128 contiguous
-// bytes; its 16-byte chunk q (8 halves of K) sits at chunk position
-// q ^ ((r >> 1) & 7).  The swizzle is applied on the global side of the direct
-// global->LDS loads (a wave's load always fills 1 KB of consecutive LDS).  The
-// LDS serves 256 B (64 banks) per cycle, i.e. 16 lanes of a 16-byte read: 16
-// consecutive rows reading the same chunk then touch 16 different 16-byte
-// bank groups (measured: no bank-conflict cycles; with q ^ (r & 7) half of
-// the LDS cycles were conflicts).
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef const __attribute__((address_space(1))) void global_void_t;
-
-// Scheduling hint for one pipeline phase: first the 2 * kVmem global->LDS loads
-// and the kReads LDS reads that fetch the next phase's fragments, then the
-// kMfma MFMAs on the fragments read one phase earlier.  The reads then have a
-// whole phase of MFMA time to land, so no MFMA waits on a read just issued.
-template <int kReads, int kMfma, int kVmem> __device__ __forceinline__ void order_phase()
-{
-    if constexpr (kVmem > 0) __builtin_amdgcn_sched_group_barrier(0x020, 2 * kVmem, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, kMfma, 0);
-    __builtin_amdgcn_sched_barrier(0);
-}
-
 // kWM x kWN waves per workgroup; each wave owns a (256 / kWM) x (256 / kWN)
 // piece of the tile as TM x TN MFMA tiles of 32 x 32.
 template <int kWM, int kWN>
@@ -192,20 +108,12 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
     const int64_t row_step = kWaves * 8 * ld * 2;   // bytes between wave-loads i and i + 1
 
     auto issue_loads = [&](int kt, int stage) {
-#ifdef FGMP_DBG_NOLOAD
-        if (kt > 1) return;
-#endif
 #pragma unroll
         for (int i = 0; i < kLoads; ++i) {
             __builtin_amdgcn_global_load_lds((global_void_t *)(ga + i * row_step + (int64_t)kt * kRowBytes),
                                              (lds_void_t *)&lds[stage][0][(kWaves * i + wave) * 1024], 16, 0, 0);
-#ifdef FGMP_DBG_BTHIRD
-            if (i % 3 == 0)
-#endif
-#ifndef FGMP_DBG_NOB
             __builtin_amdgcn_global_load_lds((global_void_t *)(gb + i * row_step + (int64_t)kt * kRowBytes),
                                              (lds_void_t *)&lds[stage][1][(kWaves * i + wave) * 1024], 16, 0, 0);
-#endif
         }
     };
 
@@ -224,24 +132,13 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
         frag_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
     auto read_frags = [&](int stage, int kk, half8_t (&a)[TM], half8_t (&b)[TN]) {
-#ifdef FGMP_DBG_NOLDSREAD
-        if (kk >= 0) return;
-#endif
         const char *la = &lds[stage][0][wm * (TM * 32) * kRowBytes], *lb = &lds[stage][1][wn * (TN * 32) * kRowBytes];
-#ifndef FGMP_DBG_NOAREAD
 #pragma unroll
         for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const half8_t *>(la + i * 32 * kRowBytes + frag_off[kk]);
-#endif
-#ifndef FGMP_DBG_NOBREAD
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const half8_t *>(lb + j * 32 * kRowBytes + frag_off[kk]);
-#endif
     };
     auto mfma_block = [&](const half8_t (&a)[TM], const half8_t (&b)[TN]) {
-#ifdef FGMP_DBG_NOMFMA
-        acc[0][0][0] += (float)a[0][0] * (float)b[0][0] + (float)a[TM - 1][7] * (float)b[TN - 1][7];
-        return;
-#endif
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -274,10 +171,8 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
         read_frags(st, 3, fa[1], fb[1]);
         mfma_block(fa[0], fb[0]);
         order_phase<kReads, kMfma, 0>();
-#ifndef FGMP_DBG_NOBARRIER
         __builtin_amdgcn_s_waitcnt(0);   // own LDS reads done, own global->LDS loads landed
         __syncthreads();
-#endif
         // the last two iterations reload the final K-step, which nobody reads again
         issue_loads(kt + 2 < nk ? kt + 2 : nk - 1, st);
         read_frags(st ^ 1, 0, fa[0], fb[0]);
@@ -299,11 +194,7 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = tm * kBM + wm * (TM * 32) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-#ifdef FGMP_DBG_NOSTORE
-                if (row < M && col < N && acc[i][j][r] == 12345.678f) Y[row * ldy + col] = acc[i][j][r] * ss;
-#else
                 if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
-#endif
             }
         }
 }
@@ -330,6 +221,17 @@ static GemmWorkspace gemm_ws_layout(int64_t M, int64_t N, int64_t K)
     w.off_b = (size_t)align_up((uint64_t)w.Mp * w.ld * 2, 256);
     w.total = w.off_b + (size_t)align_up((uint64_t)w.Np * w.ld * 2, 256);
     return w;
+}
+
+// FGMP_PREFILL_KERNEL=dense selects the two-pass path (both operands expanded to FP16 in the
+// workspace, then a plain FP16 kernel); the default decodes the weights inside the MFMA kernel.
+static bool prefill_decodes_in_kernel()
+{
+    static const bool in_kernel = [] {
+        const char *e = getenv("FGMP_PREFILL_KERNEL");
+        return !(e && e[0] == 'd');
+    }();
+    return in_kernel;
 }
 
 constexpr int64_t kSkinnyMaxM = 32;   // at most this many rows of X take the weight-streaming path
@@ -359,6 +261,17 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
     const PackedView B = make_view(const_cast<void *>(packed_W), lb);
     if (M <= kSkinnyMaxM) return gemm_skinny(A, la, B, lb, M, N, K, Y, ldy, workspace, st);
     const GemmWorkspace w = gemm_ws_layout(M, N, K);
+    if (prefill_decodes_in_kernel()) {
+        // activations expanded to FP16 once (M x K is small); weights decoded inside the MFMA kernel
+        _Float16 *x16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
+        const int64_t tiles_m = w.Mp / kBM, tiles_n = w.Np / kBN;
+        if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
+        const DecodeJob jx = make_decode_job(A, la, x16, w.ld, w.Mp / kTileRows);
+        const fgmp_status_t rcx = launch_decode_f16(jx, nullptr, nullptr, 0, st);
+        if (rcx != FGMP_OK) return rcx;
+        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, A.hdr, st);
+        return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+    }
     _Float16 *a16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
     _Float16 *b16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_b);
     const int64_t n_tm = w.Mp / kBM, n_tn = w.Np / kBN;

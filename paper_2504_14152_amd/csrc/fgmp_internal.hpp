@@ -40,6 +40,9 @@ struct DecodeJob {
 DecodeJob make_decode_job(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad);
 fgmp_status_t launch_decode_f16(const DecodeJob &a, const DecodeJob *b, uint32_t *zero, int64_t zero_n,
                                 hipStream_t st);
+void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
+                       int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
+                       hipStream_t st);
 fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);

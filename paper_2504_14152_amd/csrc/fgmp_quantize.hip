@@ -345,9 +345,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(PackedView v, PackedLayout 
 
 static int pick_rt_per_wave(int64_t n_rt)
 {
-#ifdef FGMP_DBG_RTPW
-    if (const char *e = getenv("FGMP_RTPW")) return atoi(e);
-#endif
+
     // enough work per wave to amortize the sensitivity loads, enough workgroups to fill 256 CUs
     if (n_rt >= 4096) return 4;
     if (n_rt >= 1024) return 2;

@@ -318,3 +318,23 @@ def test_gemm_decode_shapes(M, K, N, p):
     assert torch.equal(Y, Y2), "split-K combination must be deterministic"
     Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
     assert torch.equal(Y, Yf)
+
+
+def test_gemm_two_pass_path_in_subprocess():
+    """The alternative prefill path (both operands expanded to FP16 first) is chosen
+    once per process by FGMP_PREFILL_KERNEL=dense; check it in a child process."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np, torch, sys\n"
+        "sys.path.insert(0, %r)\n"
+        "import tests.test_gpu_parity as t\n"
+        "c = t._quantized_pair(200, 1040, 264, 7, 0.2)\n"
+        "Y = t.fgmp.gemm(c['pX'], c['pW'])\n"
+        "t._check_gemm(c, Y, label='two-pass')\n"
+        "print('two-pass ok')\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, FGMP_PREFILL_KERNEL="dense")
+    res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110)
+    assert res.returncode == 0 and "two-pass ok" in res.stdout, res.stdout + res.stderr
