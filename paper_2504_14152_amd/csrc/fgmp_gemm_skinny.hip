@@ -15,11 +15,14 @@
 // read from LDS with the same assignment.  The FP8 blocks' upper halves (plane
 // H) of a tile are fetched speculatively, 32 entries per tile per wave, and
 // handed to the lane that needs them with ds_bpermute.
-#include "fgmp_internal.hpp"
+#include <atomic>
+#include <chrono>
+#include <random>
+
+#include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
 
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kSkRows = 64;       // weight rows per workgroup
@@ -28,6 +31,38 @@ constexpr int kSkPrefetch = 4;    // K-tiles in flight per wave
 constexpr int kSkXPad = 8;        // halves of padding per LDS activation row
 constexpr int kSkSpec = 32;       // plane-H entries fetched speculatively per tile
 
+constexpr int kSkSumPass = 4;     // partial tiles summed per pass (their loads are in flight together)
+constexpr int kSkMaxSplit = 16;   // most K ranges per row group the planner asks for
+
+// 16-byte accesses to the partial-sum buffer that are coherent across XCDs: buffer instructions with
+// the sc0 sc1 cache policy (system scope) bypass the per-XCD L2; being ordinary loads and stores,
+// the compiler tracks their completion itself.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kCoherent = 1 | 16;   // sc0 | sc1
+__device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off, float4_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), buf, (int)byte_off, 0, kCoherent);
+}
+__device__ __forceinline__ float4_t load_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off)
+{
+    return __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(buf, (int)byte_off, 0, kCoherent));
+}
+
+// Arrival counter of a row group that needs no clearing between calls: the word holds
+// (epoch << 8) | count, and a value left by an earlier call (or never initialised) carries a
+// different 56-bit epoch and is treated as zero.  Returns how many workgroups arrived before.
+__device__ __forceinline__ uint32_t arrive(unsigned long long *ctr, unsigned long long epoch)
+{
+    unsigned long long old = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {
+        const bool same = (old >> 8) == epoch;
+        const unsigned long long want = same ? old + 1 : ((epoch << 8) | 1ull);
+        if (__hip_atomic_compare_exchange_strong(ctr, &old, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT))
+            return same ? (uint32_t)(old & 0xFFull) : 0u;
+    }
+}
+
 struct SkinnyStage {
     uint4 l;       // blocks 2g, 2g+1 of this lane's row
     uint32_t s;    // their two scale-or-index bytes
@@ -35,11 +70,11 @@ struct SkinnyStage {
 };
 
 template <int MT>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLayout lw, const _Float16 *Xh,
-                                                           int64_t ldx, int cols_per_wg, int ksplit,
-                                                           float *partial, uint32_t *counters, float *Y,
-                                                           int64_t ldy, int64_t M, int64_t N,
-                                                           const PackedHeader *hx)
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLayout lw, PackedView X,
+                                                           PackedLayout lx, int cols_per_wg, int ksplit,
+                                                           float *partial, uint32_t partial_bytes,
+                                                           unsigned long long *counters, unsigned long long epoch,
+                                                           float *Y, int64_t ldy, int64_t M, int64_t N)
 {
     constexpr int kXRow = kSkMaxCols * kTileK + kSkXPad;
     __shared__ __attribute__((aligned(16))) _Float16 xs[16 * MT][kXRow];
@@ -54,7 +89,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLa
     // The header is only used to zero the result of a mismatched operand; no load
     // address depends on it, so the stream starts without waiting for this load.
     const PackedHeader wh = *W.hdr;
-    const float sx = hx->tensor_scale;
+    const PackedHeader xh = *X.hdr;
 
     const int nl = lane & 15, g = lane >> 4;
     const int64_t rtA = rg * (kSkRows / kTileRows) + wave * 2;   // the wave's two row-tiles: rtA, rtA + 1
@@ -94,23 +129,26 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLa
 #pragma unroll
     for (int p = 0; p < kSkPrefetch; ++p) issue_ls(p, ring[p]);
 
-    // activations of this K range -> LDS through registers (all loads first)
+    // activations of this K range: packed tiles (8 rows x 128 K, one block per lane) decoded straight
+    // into LDS; 2 MT row-tiles x ncols K-tiles, spread over the 4 waves
     {
-        constexpr int kChunksPerRow = kSkMaxCols * (kTileK / 8);   // 128 chunks of 16 B
-        constexpr int kIters = 16 * MT * kChunksPerRow / 256;
-        uint4 xr[kIters];
-#pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            const int i = tid + 256 * it, m = i / kChunksPerRow, ch = i % kChunksPerRow;
-            const int chc = ch < ncols * (kTileK / 8) ? ch : 0;
-            xr[it] = *reinterpret_cast<const uint4 *>(Xh + (int64_t)m * ldx + c0 * kTileK + chc * 8);
-        }
 #pragma unroll
         for (int p = 0; p < kSkPrefetch; ++p) issue_h(p, ring[p]);
+        const bool x_ok = xh.magic == kMagic && xh.rows == lx.rows && xh.K == lx.K;
+        const int n_xt = 2 * MT * ncols;
+        for (int i = wave; i < n_xt; i += 4) {
+            const int xrt = i / ncols, xc = i % ncols;
+            half2_t vals[8];
+            if (xrt < lx.n_rt && x_ok) {
+                decode_slot(X, (int64_t)xrt * lx.n_kt + c0 + xc, lane, vals);
+            } else {
 #pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            const int i = tid + 256 * it, m = i / kChunksPerRow, ch = i % kChunksPerRow;
-            if (ch < ncols * (kTileK / 8)) *reinterpret_cast<uint4 *>(&xs[m][ch * 8]) = xr[it];
+                for (int j = 0; j < 8; ++j) vals[j] = half2_t{(_Float16)0.0f, (_Float16)0.0f};
+            }
+            const uint32_t *w = reinterpret_cast<const uint32_t *>(vals);
+            uint4 *dst = reinterpret_cast<uint4 *>(&xs[xrt * kTileRows + (lane >> 3)][xc * kTileK + (lane & 7) * kBlock]);
+            dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
         }
     }
     __syncthreads();
@@ -210,7 +248,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLa
 
     // acc[mt][r] = partial Y[m = 16 mt + 4 (lane / 16) + r][n = 64 rg + 16 wave + lane % 16]
     const bool w_ok = wh.magic == kMagic && wh.rows == lw.rows && wh.K == lw.K;
-    const float ss = w_ok ? sx * wh.tensor_scale : 0.0f;
+    const float ss = w_ok ? xh.tensor_scale * wh.tensor_scale : 0.0f;
     const int n_local = wave * 16 + nl;
     if (ksplit == 1) {
         const int64_t n = rg * kSkRows + n_local;
@@ -223,32 +261,44 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLa
             }
         return;
     }
-    float *mine = partial + ((int64_t)blockIdx.x * (16 * MT)) * kSkRows;
+    // Partial tile layout: [n_local (64)][m (16 MT)], so a lane's four accumulators of one MFMA tile
+    // (rows 4g .. 4g+3 of column n_local) are 16 contiguous bytes.  Partials and the arrival counter
+    // cross XCDs: they are written and read with system-coherent vector accesses (sc0 sc1), which
+    // bypass the per-XCD L2, and the stores are waited for before the counter is bumped, so no cache
+    // write-back or invalidate is needed.
+    constexpr uint32_t kTileBytes32 = kSkRows * (16 * MT) * 4;   // bytes of one partial tile
+    const __amdgpu_buffer_rsrc_t pbuf =
+        __builtin_amdgcn_make_buffer_rsrc(partial, 0, (int)partial_bytes, 0x00020000);
+    const uint32_t mine = (uint32_t)blockIdx.x * kTileBytes32;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            __hip_atomic_store(&mine[(mt * 16 + 4 * g + r) * kSkRows + n_local], acc[mt][r], __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-    // Partials and the arrival counter are written and read with agent-scope
-    // atomics, which bypass the per-XCD caches; waiting for the stores to
-    // complete before the counter is bumped orders them without a cache
-    // write-back.
+        store_coherent16(pbuf, mine + (uint32_t)(n_local * (16 * MT) + mt * 16 + 4 * g) * 4u, acc[mt]);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (tid == 0)
-        arrival = __hip_atomic_fetch_add(&counters[rg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) arrival = arrive(&counters[rg], epoch);
     __syncthreads();
     if (arrival != (uint32_t)(ksplit - 1)) return;
-    // last workgroup of this row group: add the partials in K order
-    const float *first = partial + (rg * ksplit * (16 * MT)) * kSkRows;
-    for (int i = tid; i < 16 * MT * kSkRows; i += 256) {
-        const int64_t m = i / kSkRows, n = rg * kSkRows + i % kSkRows;
-        float sum = 0.0f;
-        for (int k = 0; k < ksplit; ++k)
-            sum += __hip_atomic_load(&first[(int64_t)k * (16 * MT) * kSkRows + i], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
-        if (m < M && n < N) Y[m * ldy + n] = sum * ss;
+    // last workgroup of this row group: add the partials in K order, 4 rows of one column per thread
+    const uint32_t first = (uint32_t)(rg * ksplit) * kTileBytes32;
+    constexpr int kVecs = kSkRows * (16 * MT) / 4;   // 16-byte vectors per partial tile
+    for (int i = tid; i < kVecs; i += 256) {
+        float4_t sum = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int k0 = 0; k0 < ksplit; k0 += kSkSumPass) {
+            float4_t part[kSkSumPass];
+#pragma unroll
+            for (int k = 0; k < kSkSumPass; ++k) {
+                const int kk = k0 + k < ksplit ? k0 + k : ksplit - 1;
+                part[k] = load_coherent16(pbuf, first + (uint32_t)kk * kTileBytes32 + (uint32_t)i * 16u);
+            }
+#pragma unroll
+            for (int k = 0; k < kSkSumPass; ++k)
+                if (k0 + k < ksplit) sum += part[k];
+        }
+        const int64_t n = rg * kSkRows + i / (4 * MT);
+        const int64_t m0 = (i % (4 * MT)) * 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (m0 + r < M && n < N) Y[(m0 + r) * ldy + n] = sum[r] * ss;
     }
 }
 
@@ -256,8 +306,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLa
 
 struct SkinnyPlan {
     int mt, cols_per_wg, ksplit;
-    int64_t row_groups, ldx;
-    size_t off_x, off_partial, off_counters, total;
+    int64_t row_groups;
+    size_t off_partial, off_counters, total;
 };
 
 static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
@@ -266,45 +316,52 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     const PackedLayout lw = make_layout(N, K);
     p.mt = M <= 16 ? 1 : 2;
     p.row_groups = (N + kSkRows - 1) / kSkRows;
-    p.ldx = lw.n_kt * kTileK;
     // about three workgroups per CU, at most 8 K-tiles each
     int64_t want = (768 + p.row_groups - 1) / p.row_groups;
-    const int64_t need = (lw.n_kt + kSkMaxCols - 1) / kSkMaxCols;
+    int max_cols = kSkMaxCols;
+    const int64_t need = (lw.n_kt + max_cols - 1) / max_cols;
     if (want < need) want = need;
+    if (want > kSkMaxSplit) want = kSkMaxSplit;
+    if (want < need) want = need;   // long K: more ranges than one summing pass, still correct
     if (want > lw.n_kt) want = lw.n_kt;
     p.cols_per_wg = (int)((lw.n_kt + want - 1) / want);
     p.ksplit = (int)((lw.n_kt + p.cols_per_wg - 1) / p.cols_per_wg);
-    p.off_x = 0;
-    p.off_partial = (size_t)align_up((uint64_t)(16 * p.mt) * p.ldx * 2, 256);
-    p.off_counters = p.off_partial +
-                     (size_t)align_up((uint64_t)p.row_groups * p.ksplit * (16 * p.mt) * kSkRows * 4, 256);
-    p.total = p.off_counters + (size_t)align_up((uint64_t)p.row_groups * 4, 256);
+    p.off_partial = 0;
+    p.off_counters = (size_t)align_up((uint64_t)p.row_groups * p.ksplit * (16 * p.mt) * kSkRows * 4, 256);
+    p.total = p.off_counters + (size_t)align_up((uint64_t)p.row_groups * 8, 256);
     return p;
 }
 
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return skinny_plan(M, N, K).total; }
+
+// A fresh 56-bit tag per call for the arrival counters (see arrive()).
+static unsigned long long next_epoch()
+{
+    static std::atomic<unsigned long long> counter{[] {
+        std::random_device rd;
+        return ((unsigned long long)rd() << 32) ^ rd() ^ (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
+    }()};
+    return counter.fetch_add(1) & ((1ull << 56) - 1);
+}
 
 fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
                           int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st)
 {
     const SkinnyPlan p = skinny_plan(M, N, K);
     char *ws = static_cast<char *>(workspace);
-    _Float16 *xh = reinterpret_cast<_Float16 *>(ws + p.off_x);
     float *partial = reinterpret_cast<float *>(ws + p.off_partial);
-    uint32_t *counters = reinterpret_cast<uint32_t *>(ws + p.off_counters);
-    if (p.row_groups * p.ksplit > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
-    const int64_t n_rt_pad = (16 * p.mt) / kTileRows;
-    // one launch decodes the activations and clears the arrival counters
-    const DecodeJob jx = make_decode_job(X, lx, xh, p.ldx, n_rt_pad);
-    const fgmp_status_t rc = launch_decode_f16(jx, nullptr, counters, p.ksplit > 1 ? p.row_groups : 0, st);
-    if (rc != FGMP_OK) return rc;
+    unsigned long long *counters = reinterpret_cast<unsigned long long *>(ws + p.off_counters);
+    const size_t partial_bytes = p.off_counters - p.off_partial;
+    if (p.row_groups * p.ksplit > 0x7FFFFFFF || partial_bytes > 0x7FFFFFFFu || p.ksplit > 255)
+        return FGMP_ERR_UNSUPPORTED;
+    const unsigned long long epoch = next_epoch();
     const dim3 grid((unsigned)(p.row_groups * p.ksplit));
     if (p.mt == 1)
-        hipLaunchKernelGGL((gemm_skinny_kernel<1>), grid, dim3(256), 0, st, W, lw, xh, p.ldx, p.cols_per_wg,
-                           p.ksplit, partial, counters, Y, ldy, M, N, X.hdr);
+        hipLaunchKernelGGL((gemm_skinny_kernel<1>), grid, dim3(256), 0, st, W, lw, X, lx, p.cols_per_wg, p.ksplit,
+                           partial, (uint32_t)partial_bytes, counters, epoch, Y, ldy, M, N);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<2>), grid, dim3(256), 0, st, W, lw, xh, p.ldx, p.cols_per_wg,
-                           p.ksplit, partial, counters, Y, ldy, M, N, X.hdr);
+        hipLaunchKernelGGL((gemm_skinny_kernel<2>), grid, dim3(256), 0, st, W, lw, X, lx, p.cols_per_wg, p.ksplit,
+                           partial, (uint32_t)partial_bytes, counters, epoch, Y, ldy, M, N);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }
 
