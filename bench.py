@@ -31,6 +31,7 @@ METRIC = "FGMP GEMM TFLOP/s + act-quant GB/s, Llama-2-7B linear shapes, 10% FP8 
 PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense FP16/BF16 matrix peak
 PEAK_HBM_GBPS = 8000.0
 P_FP8 = 0.10
+PREHEAT_S = 0.08                # untimed load before the warm-up steps (clock ramp)
 # HBM-side bytes of one gemm_mixed_kernel launch on this workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (KiB per dispatch; FETCH_SIZE reads half of a known-size copy's bytes and is scaled by 2,
 # WRITE_SIZE reads it exactly): see profiles/gemm_mixed_kernel_qkv_prefill_traffic.txt
@@ -45,8 +46,8 @@ def bytes_per_block(p: float) -> float:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--sweep", action="store_true",
@@ -71,7 +72,12 @@ def main() -> int:
         bits = synth.f32_to_bf16_bits(x32)
         return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16), bits
 
-    def timed(fn, iters, warm):
+    def timed(fn, iters, warm, heat_s=0.05):
+        t_heat = time.perf_counter()
+        while time.perf_counter() - t_heat < heat_s:   # untimed: leave the idle clock state (see below)
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
@@ -116,6 +122,14 @@ def main() -> int:
         fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW, out=Y, workspace=ws)
 
     # ------------------------------------------------------------ timed region: K whole steps
+    # After the host-side setup above the GPU sits in a low clock state and needs some tens of
+    # milliseconds of load to leave it (the first ~30 steps run about 15% slower than the rest); the
+    # pre-heat below is untimed, like the W warm-up steps that follow it.
+    t_pre = time.perf_counter()
+    while time.perf_counter() - t_pre < PREHEAT_S:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -132,26 +146,27 @@ def main() -> int:
     value = flops / (ms_step * 1e-3) / 1e12
 
     # dominant kernel: gemm_mixed_kernel (MFMA kernel that decodes the packed weights itself).  A step
-    # launches three kernels back to back -- quantizer, the pass that expands the activations to FP16,
-    # and this kernel -- so its average duration over the timed region is the step time minus the two
-    # small kernels timed on their own (events on the launch stream).
-    ms_gemm = timed(lambda: fgmp.gemm(pX, pW, out=Y, workspace=ws), args.steps, 2)
-    ms_quant = timed(lambda: fgmp.quantize_activations(xd, fxd, Tx, sx, out=pX), args.steps, 2)
-    x16 = fgmp.dequantize_f16(pX)
-    ms_dec_x = timed(lambda: fgmp.dequantize_f16(pX, out=x16), args.steps, 2)
+    # launches two kernels back to back -- the quantizer, which writes the FP16 values of the codes it
+    # selects, and this kernel -- so its average duration over the timed region is the step time minus
+    # the quantizer's, timed on its own through fgmp_quantize_dequantize_f16 (events on the launch stream).
+    x16 = fgmp.quantize_dequantize_f16(xd, fxd, Tx, sx)
+    ms_quant16 = timed(lambda: fgmp.quantize_dequantize_f16(xd, fxd, Tx, sx, out=x16), args.steps, 20)
     del x16
-    ms_kernel = max(ms_step - ms_quant - ms_dec_x, 1e-6)
+    ms_kernel = max(ms_step - ms_quant16, 1e-6)
     achieved = flops / (ms_kernel * 1e-3) / 1e12
+    # the same product from packed activations (fgmp_gemm: expands X to FP16 first), and the packing quantizer
+    ms_gemm = timed(lambda: fgmp.gemm(pX, pW, out=Y, workspace=ws), args.steps, 20)
+    ms_quant = timed(lambda: fgmp.quantize_activations(xd, fxd, Tx, sx, out=pX), args.steps, 20)
     roofline = {"bound": "mfma", "kernel": "gemm_mixed_kernel", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
                 "traffic": GEMM_KERNEL_HBM_BYTES, "ms_per_launch": round(ms_kernel, 4),
-                "gemm_call_alone": {"ms": round(ms_gemm, 4), "TFLOPs": round(flops / (ms_gemm * 1e-3) / 1e12, 2),
-                                    "ms_decode_x": round(ms_dec_x, 4)}}
+                "ms_quantize_to_f16": round(ms_quant16, 4),
+                "gemm_call_alone": {"ms": round(ms_gemm, 4), "TFLOPs": round(flops / (ms_gemm * 1e-3) / 1e12, 2)}}
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic", "preheat_ms": PREHEAT_S * 1e3,
         "config": {"workload": "Llama-2-7B fused QKV prefill (configs[1]): X 4096x4096 bf16, 1% channels x20; "
                                "W 12288x4096 N(0,0.02) packed FGMP; 10% FP8 blocks in weights and activations; "
                                "step = fgmp_quant_gemm_fused",
@@ -245,7 +260,7 @@ def main() -> int:
         del sc_x
         Yp = torch.empty((Mp_, Np_), dtype=torch.float32, device=dev)
         wsp = torch.empty(fgmp.workspace_bytes(Mp_, Np_, Kp_), dtype=torch.uint8, device=dev)
-        ms_p = timed(lambda: fgmp.quant_gemm_fused(xp, fxp, Txp, sxp, pWp, out=Yp, workspace=wsp), 10, 5)
+        ms_p = timed(lambda: fgmp.quant_gemm_fused(xp, fxp, Txp, sxp, pWp, out=Yp, workspace=wsp), 50, 10)
         info = fgmp.packed_info(pWp)
         return {"ms_per_step": round(ms_p, 4), "TFLOPs": round(2.0 * Mp_ * Np_ * Kp_ / (ms_p * 1e-3) / 1e12, 1),
                 "frac_mfma_peak": round(2.0 * Mp_ * Np_ * Kp_ / (ms_p * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS, 4),

@@ -149,6 +149,24 @@ fgmp_status_t fgmp_dequantize_f16(const void *packed, int64_t rows, int64_t K, v
                                   int64_t ld, void *stream);
 
 /*
+ * Quantize activations (Sec. 3.1-3.3, Eq. 6; same selection as
+ * fgmp_quantize_activations) and write, instead of the packed codes, the FP16
+ * value of every stored code: the "quantize then dequantize" form of X that the
+ * fused prefill path feeds to the GEMM.  Bit-identical to
+ * fgmp_quantize_activations followed by fgmp_dequantize_f16; the tensor scale
+ * is not applied (x_hat = tensor_scale * out).
+ *   X, dt, M, K, ldx, fisher_k, threshold, tensor_scale   as fgmp_quantize_activations
+ *   out   device, rows_out x ld halves, 16-byte aligned; rows_out >= M rounded
+ *         up to a multiple of 8; ld >= K rounded up to a multiple of 128 and a
+ *         multiple of 8; rows M.. of the last 8-row group and columns K.. of the
+ *         last 128-column group are written as zeros, nothing beyond them
+ * Errors: as fgmp_quantize_activations; FGMP_ERR_BAD_SHAPE for rows_out / ld.
+ */
+fgmp_status_t fgmp_quantize_dequantize_f16(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                           const float *fisher_k, float threshold, float tensor_scale,
+                                           void *out, int64_t rows_out, int64_t ld, void *stream);
+
+/*
  * Offline helpers.  These synchronize `stream` and use host memory.
  */
 

@@ -53,18 +53,8 @@ fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, i
                                     const void *packed_W, int64_t N, float *Y, int64_t ldy,
                                     void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!workspace) return FGMP_ERR_INVALID_ARG;
-    if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
-    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
-    if ((uintptr_t)workspace % 16 != 0) return FGMP_ERR_BAD_ALIGN;
-    const size_t xbytes = (size_t)make_layout(M, K).total_bytes;
-    if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
-    fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, workspace, xbytes,
-                                       nullptr, /*compact=*/false, as_stream(stream));
-    if (rc != FGMP_OK) return rc;
-    char *rest = static_cast<char *>(workspace) + xbytes;
-    return gemm_packed(workspace, M, packed_W, N, K, Y, ldy, rest, workspace_bytes - xbytes,
-                       as_stream(stream));
+    return quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Y, ldy, workspace,
+                      workspace_bytes, as_stream(stream));
 }
 
 fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K, uint8_t *codes,
@@ -86,6 +76,17 @@ fgmp_status_t fgmp_dequantize_f16(const void *packed, int64_t rows, int64_t K, v
     const fgmp_status_t rc = launch_decode_f16(job, nullptr, nullptr, 0, as_stream(stream));
     if (rc != FGMP_OK) return rc;
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
+fgmp_status_t fgmp_quantize_dequantize_f16(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                           const float *fisher_k, float threshold, float tensor_scale,
+                                           void *out, int64_t rows_out, int64_t ld, void *stream)
+{
+    if (!out || M <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    if (rows_out < (M + kTileRows - 1) / kTileRows * kTileRows) return FGMP_ERR_BAD_SHAPE;
+    return quantize_tensor(X, dt, M, K, ldx, fisher_k, /*ld_fisher=*/0, threshold, tensor_scale, nullptr, 0,
+                           nullptr, /*compact=*/false, as_stream(stream), static_cast<_Float16 *>(out), ld);
 }
 
 fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host, void *stream)

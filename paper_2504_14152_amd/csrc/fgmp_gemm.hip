@@ -286,4 +286,39 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }
 
+// Fused call.  Prefill shapes: the quantizer writes the FP16 values of the codes
+// it selects straight into the GEMM's A operand (the packed form of X is never
+// materialized; only its header, which carries the tensor scale).  Other shapes
+// and the two-pass path go through the packed activations.
+fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
+                         float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
+                         void *workspace, size_t workspace_bytes, hipStream_t st)
+{
+    if (!workspace || !packed_W || !Y) return FGMP_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0 || ldy < N) return FGMP_ERR_BAD_SHAPE;
+    if (((uintptr_t)workspace | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
+    if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    if (M > kSkinnyMaxM && prefill_decodes_in_kernel() && kUseHwCvt) {
+        const GemmWorkspace w = gemm_ws_layout(M, N, K);
+        const int64_t tiles_m = w.Mp / kBM, tiles_n = w.Np / kBN;
+        if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
+        PackedHeader *hx = reinterpret_cast<PackedHeader *>(ws);
+        _Float16 *x16 = reinterpret_cast<_Float16 *>(ws + kHeaderBytes);
+        const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws,
+                                                 sizeof(PackedHeader), nullptr, false, st, x16, w.ld);
+        if (rc != FGMP_OK) return rc;
+        const PackedLayout lb = make_layout(N, K);
+        const PackedView B = make_view(const_cast<void *>(packed_W), lb);
+        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, hx, st);
+        return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+    }
+    const size_t xbytes = (size_t)make_layout(M, K).total_bytes;
+    const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws, xbytes,
+                                             nullptr, false, st);
+    if (rc != FGMP_OK) return rc;
+    return gemm_packed(ws, M, packed_W, N, K, Y, ldy, ws + xbytes, workspace_bytes - xbytes, st);
+}
+
 }  // namespace fgmp

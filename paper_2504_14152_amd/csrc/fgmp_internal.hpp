@@ -20,12 +20,17 @@ constexpr bool kUseHwCvt = FGMP_HW_CVT != 0;
 
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
-                              size_t packed_bytes, float *scores, bool compact, hipStream_t st);
+                              size_t packed_bytes, float *scores, bool compact, hipStream_t st,
+                              _Float16 *x16 = nullptr, int64_t ld16 = 0);
 fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
                             uint8_t *mask, hipStream_t st);
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
                           float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// quantize X and multiply in one call; `workspace` holds at least gemm_workspace_bytes(M, N, K)
+fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
+                         float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
+                         void *workspace, size_t workspace_bytes, hipStream_t st);
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K);
 fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
                           int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st);

@@ -38,13 +38,18 @@ struct QuantParams {
     PackedView out;
     int64_t n_rt, n_kt;
     float *scores;
-    int mode;          // kModeStrided / kModeCount / kModeCompact
+    int mode;          // kModeStrided / kModeCount / kModeCompact / kModeF16
     int rt_per_wave;
     PackedLayout layout;   // for the header, written by the first launch of a call
     uint32_t compact;
+    _Float16 *x16;         // kModeF16: dequantized values (without the tensor scale), [8 n_rt][ld16]
+    int64_t ld16;
 };
 
-enum { kModeStrided = 0, kModeCount = 1, kModeCompact = 2 };
+// kModeF16 writes, instead of the packed planes, the FP16 value of every stored
+// code (exact: an E2M1 value times an E4M3 scale, or an E4M3 value), which is
+// what the prefill GEMM consumes; only the header goes to the packed buffer.
+enum { kModeStrided = 0, kModeCount = 1, kModeCompact = 2, kModeF16 = 3 };
 
 __device__ __forceinline__ void write_header(PackedHeader *hdr, const PackedLayout &l, float S, uint32_t compact)
 {
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
     const float inv_S = 1.0f / p.S;
     const float S6 = 6.0f * p.S;
     if constexpr (kMode != kModeCompact) {
-        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && p.out.hdr != nullptr)
             write_header(p.out.hdr, p.layout, p.S, p.compact);
     }
 
@@ -232,6 +237,40 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
 
         if constexpr (kMode == kModeCount) {
             if (lane == 0) p.out.T[tile] = (uint32_t)__popcll(ballot);
+        } else if constexpr (kMode == kModeF16) {
+            static_assert(kHW, "the FP16 output mode uses the conversion instructions");
+            half2_t o[8];
+            if (hi) {
+                float r[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                uint32_t c[4];
+                if (amax * inv_S > 448.0f) encode_fp8_block<kHW, true>(r, c);
+                else encode_fp8_block<kHW, false>(r, c);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    o[2 * j] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(c[j], 1.0f, false);
+                    o[2 * j + 1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(c[j], 1.0f, true);
+                }
+            } else {
+                const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sc | (sc << 8), 1.0f, false);
+                o[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 0) * s;
+                o[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 1) * s;
+                o[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 2) * s;
+                o[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 3) * s;
+                o[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 0) * s;
+                o[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 1) * s;
+                o[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 2) * s;
+                o[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 3) * s;
+            }
+            // every slot of the tile is written (zeros where the tensor ends), so the GEMM can read whole tiles
+            union { half2_t h[8]; uint4 v[2]; } pack;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) pack.h[j] = o[j];
+            uint4 *dst = reinterpret_cast<uint4 *>(p.x16 + (rt * kTileRows + rloc) * p.ld16 +
+                                                   (kt * kTileBlocks + (lane & 7)) * kBlock);
+            dst[0] = pack.v[0];
+            dst[1] = pack.v[1];
         } else {
             const uint32_t prefix = (uint32_t)__popcll(ballot & ((1ull << lane) - 1ull));
             uint32_t hbase;
@@ -367,15 +406,17 @@ static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipS
     switch (p.mode) {
     case kModeStrided: launch_quantize_mode<Tin, kModeStrided>(p, per_elem, grid, st); break;
     case kModeCount: launch_quantize_mode<Tin, kModeCount>(p, per_elem, grid, st); break;
+    case kModeF16: launch_quantize_mode<Tin, kModeF16>(p, per_elem, grid, st); break;
     default: launch_quantize_mode<Tin, kModeCompact>(p, per_elem, grid, st); break;
     }
 }
 
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
-                              size_t packed_bytes, float *scores, bool compact, hipStream_t st)
+                              size_t packed_bytes, float *scores, bool compact, hipStream_t st,
+                              _Float16 *x16, int64_t ld16)
 {
-    if (!X || !fisher || !packed) return FGMP_ERR_INVALID_ARG;
+    if (!X || !fisher || (!packed && !x16)) return FGMP_ERR_INVALID_ARG;
     if (rows <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (!(S > 0.0f) || !(S < INFINITY) || T != T) return FGMP_ERR_INVALID_ARG;
     if (dt != FGMP_F32 && dt != FGMP_BF16) return FGMP_ERR_UNSUPPORTED;
@@ -386,13 +427,21 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
         (ldx * esz) % 16 != 0 || (ld_fisher * 4) % 16 != 0)
         return FGMP_ERR_BAD_ALIGN;
     const PackedLayout l = make_layout(rows, K);
-    if (packed_bytes < l.total_bytes) return FGMP_ERR_BUFFER_TOO_SMALL;
+    if (x16 != nullptr) {
+        // FP16 output: the packed buffer only receives the header
+        if (compact || !kUseHwCvt) return FGMP_ERR_UNSUPPORTED;
+        if (packed && packed_bytes < sizeof(PackedHeader)) return FGMP_ERR_BUFFER_TOO_SMALL;
+        if (ld16 < l.n_kt * kTileK || (uintptr_t)x16 % 16 != 0 || (ld16 * 2) % 16 != 0) return FGMP_ERR_BAD_SHAPE;
+    } else if (packed_bytes < l.total_bytes) {
+        return FGMP_ERR_BUFFER_TOO_SMALL;
+    }
 
     QuantParams p;
     p.X = X; p.ldx = ldx; p.rows = rows; p.nb = l.nb;
     p.fisher = fisher; p.ld_fisher = ld_fisher;
     p.T = T; p.S = S;
-    p.out = make_view(packed, l);
+    if (packed) p.out = make_view(packed, l);
+    else p.out = PackedView{};
     p.n_rt = l.n_rt; p.n_kt = l.n_kt;
     p.scores = scores;
     p.rt_per_wave = pick_rt_per_wave(l.n_rt);
@@ -404,7 +453,12 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
 
     p.layout = l;
     p.compact = compact ? 1u : 0u;
-    if (!compact) {
+    p.x16 = x16; p.ld16 = ld16;
+    if (x16 != nullptr) {
+        p.mode = kModeF16;
+        if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);
+        else launch_quantize<uint16_t>(p, per_elem, grid, st);
+    } else if (!compact) {
         p.mode = kModeStrided;
         if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);
         else launch_quantize<uint16_t>(p, per_elem, grid, st);

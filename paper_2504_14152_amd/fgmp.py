@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
     L.fgmp_unpack_canonical.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     L.fgmp_dequantize_f16.restype = ctypes.c_int
     L.fgmp_dequantize_f16.argtypes = [vp, i64, i64, vp, i64, i64, vp]
+    L.fgmp_quantize_dequantize_f16.restype = ctypes.c_int
+    L.fgmp_quantize_dequantize_f16.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, i64, vp]
     L.fgmp_packed_info.restype = ctypes.c_int
     L.fgmp_packed_info.argtypes = [vp, ctypes.POINTER(_PackedInfo), vp]
     L.fgmp_threshold_for_fraction.restype = ctypes.c_int
@@ -201,6 +203,20 @@ def dequantize_f16(p: Packed, out: torch.Tensor | None = None) -> torch.Tensor:
         out = torch.empty((-(-p.rows // 8) * 8, ld), dtype=torch.float16, device=p.buf.device)
     rc = lib().fgmp_dequantize_f16(_ptr(p.buf), p.rows, p.K, _ptr(out), out.shape[0], out.stride(0), _stream())
     _check(rc, "fgmp_dequantize_f16")
+    return out
+
+
+def quantize_dequantize_f16(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, tensor_scale: float,
+                            out: torch.Tensor | None = None) -> torch.Tensor:
+    """FP16 values of the codes the quantizer selects (without the tensor scale), [rows_out, ld]."""
+    _require_cuda(X, fisher_k)
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((-(-M // 8) * 8, -(-K // 128) * 128), dtype=torch.float16, device=X.device)
+    rc = lib().fgmp_quantize_dequantize_f16(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                            float(threshold), float(tensor_scale), _ptr(out), out.shape[0],
+                                            out.stride(0), _stream())
+    _check(rc, "fgmp_quantize_dequantize_f16")
     return out
 
 

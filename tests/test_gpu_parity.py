@@ -181,6 +181,27 @@ def test_dequantize_f16_is_exact(rows, K, p):
     assert not got[rows:].any() and not got[:, K:].any()
 
 
+@pytest.mark.parametrize("rows,K,p,scale_div", [(61, 208, 0.25, 1.0), (256, 1024, 0.1, 1.0), (19, 16, 1.0, 1.0),
+                                                 (40, 400, 0.5, 8.0), (8, 128, 0.0, 1.0)])
+def test_quantize_dequantize_f16_is_exact(rows, K, p, scale_div):
+    """Quantizer writing FP16 values directly: equal to the oracle's decode of
+    the oracle's codes, zero in the padding, untouched beyond it."""
+    _say(f"quantize_dequantize_f16 {rows}x{K} p={p} S/={scale_div}")
+    x = synth.activations(rows, K, 8, 71, outlier_count=3)
+    f = synth.fisher_per_channel(K, 8, 72)
+    S = float(synth.default_tensor_scale(x)) / scale_div
+    T = orc.threshold(orc.quantize(x, f, np.inf, S)["scores"], p)
+    want = orc.quantize(x, f, T, S)
+    ref = orc.dequantize(want["codes"], want["scales"], want["mask"])
+    r8, k128 = -(-rows // 8) * 8, -(-K // 128) * 128
+    out = torch.full((r8 + 8, k128 + 128), 7.0, dtype=torch.float16, device=DEV)
+    fgmp.quantize_dequantize_f16(torch.from_numpy(x).to(DEV), torch.from_numpy(f).to(DEV), T, S, out=out)
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:rows, :K].astype(np.float64), ref)
+    assert not got[rows:r8, :k128].any() and not got[:r8, K:k128].any()
+    assert (got[r8:] == 7.0).all() and (got[:, k128:] == 7.0).all()
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)
@@ -289,6 +310,37 @@ def test_gemm_llama_qkv_prefill_sampled():
     _check_gemm(c, Y, rows, cols, label="qkv prefill sampled")
     assert torch.isfinite(Y).all()
     Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    assert torch.equal(Y, Yf)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_fused_prefill_saturating_tensor_scale(dtype):
+    """Fused call on a prefill shape with a caller-chosen activation scale four
+    times below amax / 448: FP8 blocks saturate at +-448, and the fused path
+    (which writes FP16 values instead of packed codes) must agree with the
+    oracle and, bit for bit, with quantize-then-multiply."""
+    M, K, N, p = 136, 272, 72, 0.4
+    _say(f"fused prefill saturating scale dtype={dtype}")
+    x = synth.activations(M, K, 21, 1)
+    w = synth.weights(N, K, 21, 2)
+    fx = synth.fisher_per_channel(K, 21, 3)
+    fw = synth.fisher_per_channel(K, 21, 4)
+    wd, wref = _to_dev_bf16(w)
+    if dtype == "bf16":
+        xd, xref = _to_dev_bf16(x)
+    else:
+        xref = x.astype(np.float32)
+        xd = torch.from_numpy(xref).to(DEV)
+    sx = float(synth.default_tensor_scale(xref)) / 4.0
+    sw = float(synth.default_tensor_scale(wref))
+    fxd, fwd = torch.from_numpy(fx).to(DEV), torch.from_numpy(fw).to(DEV)
+    Tx = orc.threshold(orc.quantize(xref, fx, np.inf, sx)["scores"], p)
+    Tw = orc.threshold(orc.quantize(wref, fw, np.inf, sw)["scores"], p)
+    pW = fgmp.quantize_weights(wd, fwd, Tw, sw)
+    Yf = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW)
+    c = dict(xref=xref, wref=wref, fx=fx, fw=fw, sx=sx, sw=sw, Tx=Tx, Tw=Tw)
+    _check_gemm(c, Yf, label=f"fused saturating {dtype}")
+    Y = fgmp.gemm(fgmp.quantize_activations(xd, fxd, Tx, sx), pW)
     assert torch.equal(Y, Yf)
 
 
