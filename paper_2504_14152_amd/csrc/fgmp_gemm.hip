@@ -13,6 +13,8 @@
 // operands are expanded first and a plain FP16 kernel multiplies them.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
@@ -234,16 +236,21 @@ static bool prefill_decodes_in_kernel()
     return in_kernel;
 }
 
-constexpr int64_t kSkinnyMaxM = 32;   // at most this many rows of X take the weight-streaming path
+// FP16 activations of a decode-shape call: gemm_skinny_x16_rows(M) rows
+static size_t skinny_x16_bytes(int64_t M, int64_t K)
+{
+    return (size_t)align_up((uint64_t)gemm_skinny_x16_rows(M) * round_up(K, kTileK) * 2, 256);
+}
 
 size_t gemm_only_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    return M <= kSkinnyMaxM ? gemm_skinny_workspace_bytes(M, N, K) : gemm_ws_layout(M, N, K).total;
+    return gemm_skinny_applies(M, N, K) ? skinny_x16_bytes(M, K) + gemm_skinny_workspace_bytes(M, N, K)
+                                        : gemm_ws_layout(M, N, K).total;
 }
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    // the fused call also keeps the packed activations here
+    // the fused call also keeps the quantized activations here: packed, or header + FP16 values
     return (size_t)make_layout(M, K).total_bytes + gemm_only_workspace_bytes(M, N, K);
 }
 
@@ -259,7 +266,17 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
     const PackedLayout la = make_layout(M, K), lb = make_layout(N, K);
     const PackedView A = make_view(const_cast<void *>(packed_X), la);
     const PackedView B = make_view(const_cast<void *>(packed_W), lb);
-    if (M <= kSkinnyMaxM) return gemm_skinny(A, la, B, lb, M, N, K, Y, ldy, workspace, st);
+    if (gemm_skinny_applies(M, N, K)) {
+        // decode shapes: expand the few activation rows to FP16 once, then stream the weights
+        _Float16 *x16 = static_cast<_Float16 *>(workspace);
+        const int64_t ld16 = round_up(K, kTileK);
+        const DecodeJob jx = make_decode_job(A, la, x16, ld16, gemm_skinny_x16_rows(M) / kTileRows);
+        char *sws = static_cast<char *>(workspace) + skinny_x16_bytes(M, K);
+        const SkinnyCounters ctr = gemm_skinny_counters(M, N, K, sws);
+        const fgmp_status_t rcx = launch_decode_f16(jx, nullptr, ctr.ptr, ctr.n, st);
+        if (rcx != FGMP_OK) return rcx;
+        return gemm_skinny(A.hdr, la, x16, ld16, packed_W, lb, M, N, K, Y, ldy, sws, st);
+    }
     const GemmWorkspace w = gemm_ws_layout(M, N, K);
     if (prefill_decodes_in_kernel()) {
         // activations expanded to FP16 once (M x K is small); weights decoded inside the MFMA kernel
@@ -300,7 +317,20 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
     if (((uintptr_t)workspace | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
     if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
-    if (M > kSkinnyMaxM && prefill_decodes_in_kernel() && kUseHwCvt) {
+    if (gemm_skinny_applies(M, N, K) && kUseHwCvt) {
+        // decode shapes: FP16 values of X (rows beyond the last 8-row group stay unwritten: they only
+        // feed output rows that are never stored), then the weight-streaming kernel
+        const int64_t ld16 = round_up(K, kTileK);
+        _Float16 *x16 = reinterpret_cast<_Float16 *>(ws + kHeaderBytes);
+        char *sws = ws + kHeaderBytes + skinny_x16_bytes(M, K);
+        const SkinnyCounters ctr = gemm_skinny_counters(M, N, K, sws);
+        const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws,
+                                                 sizeof(PackedHeader), nullptr, false, st, x16, ld16, ctr.ptr, ctr.n);
+        if (rc != FGMP_OK) return rc;
+        return gemm_skinny(reinterpret_cast<const PackedHeader *>(ws), make_layout(M, K), x16, ld16, packed_W,
+                           make_layout(N, K), M, N, K, Y, ldy, sws, st);
+    }
+    if (!gemm_skinny_applies(M, N, K) && prefill_decodes_in_kernel() && kUseHwCvt) {
         const GemmWorkspace w = gemm_ws_layout(M, N, K);
         const int64_t tiles_m = w.Mp / kBM, tiles_n = w.Np / kBN;
         if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;

@@ -15,16 +15,13 @@ constexpr int kNumXcd = 8;
 // packed -> FP16 decode
 // ---------------------------------------------------------------------------
 
-// Decode the block in slot `lane` of `tile` to 16 FP16 values with the gfx950
-// conversion instructions (exact for every code; first element in the low
-// nibble / byte).
-__device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, int lane, half2_t (&out)[8])
+// Decode one block to 16 FP16 values with the gfx950 conversion instructions
+// (exact for every code; first element in the low nibble / byte).  `lw` is the
+// block's plane-L word, `sb` its plane-S byte, `hw` its plane-H entry (only
+// used when `hi`).
+__device__ __forceinline__ void decode_block(uint2 lw, uint32_t sb, bool hi, uint2 hw, half2_t (&out)[8])
 {
-    const uint2 lw = v.L[tile * kTileSlots + lane];
-    const uint32_t sb = v.S[tile * kTileSlots + lane];
-    const uint64_t mbits = v.M[tile];
-    if ((mbits >> lane) & 1ull) {
-        const uint2 hw = v.H[(uint64_t)v.T[tile] + sb];
+    if (hi) {
         out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.x, 1.0f, false);
         out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.x, 1.0f, true);
         out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lw.y, 1.0f, false);
@@ -34,7 +31,9 @@ __device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, i
         out[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.y, 1.0f, false);
         out[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hw.y, 1.0f, true);
     } else {
-        const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sb | (sb << 8), 1.0f, false);
+        // the block scale, in both halves (the multiplies read the low half twice)
+        const half2_t s1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sb, 1.0f, false);
+        const half2_t s = half2_t{s1[0], s1[0]};
         out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 0) * s;
         out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 1) * s;
         out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 2) * s;
@@ -44,6 +43,17 @@ __device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, i
         out[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 2) * s;
         out[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.y, 1.0f, 3) * s;
     }
+}
+
+// Decode the block in slot `lane` of `tile`.
+__device__ __forceinline__ void decode_slot(const PackedView &v, int64_t tile, int lane, half2_t (&out)[8])
+{
+    const uint2 lw = v.L[tile * kTileSlots + lane];
+    const uint32_t sb = v.S[tile * kTileSlots + lane];
+    const bool hi = (v.M[tile] >> lane) & 1ull;
+    uint2 hw = make_uint2(0u, 0u);
+    if (hi) hw = v.H[(uint64_t)v.T[tile] + sb];
+    decode_block(lw, sb, hi, hw, out);
 }
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;

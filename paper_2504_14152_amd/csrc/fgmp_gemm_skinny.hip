@@ -2,10 +2,11 @@
 // packed weights are streamed from HBM exactly once and decoded in registers
 // straight into MFMA operands; the few activation rows sit in LDS as FP16.
 //
-// Work split: a workgroup owns 64 weight rows (4 waves x 16 rows) and a range
-// of at most 8 K-tiles (1024 K elements).  K ranges of one row group are
-// combined deterministically: every workgroup stores its partial tile, and the
-// last one to arrive adds the partials in K order and writes Y.
+// Work split: a workgroup owns 16 weight rows per wave (4 waves, or 8 when X has
+// more than 16 rows) and a range of at most 8 K-tiles (1024 K elements).  K
+// ranges are combined deterministically, per wave: every wave stores its
+// partial tile, and the last one to arrive adds the partials in K order and
+// writes Y.
 //
 // Lane (nl = lane % 16, g = lane / 16) of a wave reads, per K-tile of 128, the
 // 16 bytes that hold blocks 2g and 2g+1 of weight row nl -- a wave's load is
@@ -15,29 +16,34 @@
 // read from LDS with the same assignment.  The FP8 blocks' upper halves (plane
 // H) of a tile are fetched speculatively, 32 entries per tile per wave, and
 // handed to the lane that needs them with ds_bpermute.
-#include <atomic>
-#include <chrono>
-#include <random>
-
+//
+// The kernel is bound by vector-ALU issue, not by HBM, so address arithmetic is
+// kept off the vector unit: every access to the packed tensors is a buffer load
+// whose per-lane offset is computed once and whose per-K-tile displacement is an
+// immediate.  The buffer range check also makes every load safe without a
+// select: tiles past the K range or rows past the tensor read other tiles'
+// bytes or zeros, and their results are never stored.
 #include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
 
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSkRows = 64;       // weight rows per workgroup
 constexpr int kSkMaxCols = 8;     // K-tiles per workgroup
-constexpr int kSkPrefetch = 4;    // K-tiles in flight per wave
+constexpr int kSkPrefetch = 4;    // plane-L/S K-tiles in flight per wave
 constexpr int kSkXPad = 8;        // halves of padding per LDS activation row
 constexpr int kSkSpec = 32;       // plane-H entries fetched speculatively per tile
 
 constexpr int kSkSumPass = 4;     // partial tiles summed per pass (their loads are in flight together)
 constexpr int kSkMaxSplit = 16;   // most K ranges per row group the planner asks for
 
+constexpr uint32_t kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
+
 // 16-byte accesses to the partial-sum buffer that are coherent across XCDs: buffer instructions with
 // the sc0 sc1 cache policy (system scope) bypass the per-XCD L2; being ordinary loads and stores,
 // the compiler tracks their completion itself.
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kCoherent = 1 | 16;   // sc0 | sc1
 __device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off, float4_t v)
 {
@@ -48,19 +54,27 @@ __device__ __forceinline__ float4_t load_coherent16(__amdgpu_buffer_rsrc_t buf, 
     return __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(buf, (int)byte_off, 0, kCoherent));
 }
 
-// Arrival counter of a row group that needs no clearing between calls: the word holds
-// (epoch << 8) | count, and a value left by an earlier call (or never initialised) carries a
-// different 56-bit epoch and is treated as zero.  Returns how many workgroups arrived before.
-__device__ __forceinline__ uint32_t arrive(unsigned long long *ctr, unsigned long long epoch)
+__device__ __forceinline__ uint4 ld128(__amdgpu_buffer_rsrc_t b, uint32_t off, uint32_t soff = 0)
 {
-    unsigned long long old = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (;;) {
-        const bool same = (old >> 8) == epoch;
-        const unsigned long long want = same ? old + 1 : ((epoch << 8) | 1ull);
-        if (__hip_atomic_compare_exchange_strong(ctr, &old, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT))
-            return same ? (uint32_t)(old & 0xFFull) : 0u;
-    }
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(b, (int)off, (int)soff, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ uint2 ld64(__amdgpu_buffer_rsrc_t b, uint32_t off)
+{
+    const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(b, (int)off, 0, 0);
+    return make_uint2(v[0], v[1]);
+}
+__device__ __forceinline__ uint32_t ld32(__amdgpu_buffer_rsrc_t b, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(b, (int)off, 0, 0);
+}
+__device__ __forceinline__ uint32_t ld16(__amdgpu_buffer_rsrc_t b, uint32_t off, uint32_t soff = 0)
+{
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(b, (int)off, (int)soff, 0);
+}
+__device__ __forceinline__ uint32_t ld8(__amdgpu_buffer_rsrc_t b, uint32_t off)
+{
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(b, (int)off, 0, 0);
 }
 
 struct SkinnyStage {
@@ -69,243 +83,238 @@ struct SkinnyStage {
     uint2 h;       // speculative plane-H entry (lane & 31) of tile (lane >> 5)
 };
 
-template <int MT>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(PackedView W, PackedLayout lw, PackedView X,
-                                                           PackedLayout lx, int cols_per_wg, int ksplit,
-                                                           float *partial, uint32_t partial_bytes,
-                                                           unsigned long long *counters, unsigned long long epoch,
-                                                           float *Y, int64_t ldy, int64_t M, int64_t N)
-{
-    constexpr int kXRow = kSkMaxCols * kTileK + kSkXPad;
-    __shared__ __attribute__((aligned(16))) _Float16 xs[16 * MT][kXRow];
-    __shared__ uint32_t arrival;
+struct SkinnyArgs {
+    const void *w;            // packed weights (header first)
+    PackedLayout lw;
+    const PackedHeader *xh;   // header of the activations (tensor scale, shape check)
+    PackedLayout lx;
+    const _Float16 *x16;      // activations as FP16 values, [>= 16 MT rows][ld16]
+    int64_t ld16;
+    int cols_per_wg, ksplit;
+    float *partial;
+    uint32_t partial_bytes;
+    uint32_t *counters;       // one per (row group, wave), zeroed by the kernel that prepares x16
+    float *Y;
+    int64_t ldy, M, N;
+};
 
+// The code is kept small on purpose (a rolled K-tile loop with a rotating register ring instead of a
+// fully unrolled body): every launch starts with a cold instruction cache, each wave runs the code
+// once, and straight-line code of several thousand instructions made instruction fetch, not HBM, the
+// limit of this kernel.
+// kWaves waves per workgroup, 16 weight rows each; they share the activations in LDS.
+template <int MT, int kWaves>
+__global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
+{
+    constexpr int kRows = 16 * kWaves;   // weight rows per workgroup
+    constexpr int kXRow = kSkMaxCols * kTileK + kSkXPad;
+    __shared__ __attribute__((aligned(1024))) _Float16 xs[16 * MT][kXRow];
+    __shared__ uint2 m_lds[kWaves][16];       // per wave: mask words, [sel][K-tile]
+    __shared__ uint32_t t_lds[kWaves][16];    // per wave: plane-H offsets, [sel][K-tile]
+
+    const PackedLayout &lw = a.lw;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ksplit = a.ksplit;
     const int64_t rg = blockIdx.x / ksplit;
     const int ks = blockIdx.x % ksplit;
-    const int64_t c0 = (int64_t)ks * cols_per_wg;
-    const int ncols = (int)((lw.n_kt - c0 < cols_per_wg) ? lw.n_kt - c0 : cols_per_wg);
-    // The header is only used to zero the result of a mismatched operand; no load
-    // address depends on it, so the stream starts without waiting for this load.
-    const PackedHeader wh = *W.hdr;
-    const PackedHeader xh = *X.hdr;
+    const int64_t c0 = (int64_t)ks * a.cols_per_wg;
+    const int ncols = (int)((lw.n_kt - c0 < a.cols_per_wg) ? lw.n_kt - c0 : a.cols_per_wg);
+    // Headers: only the FP8 upper-half fetches (which come a round trip later anyway) and the final
+    // scaling depend on them; the plane-L stream starts without waiting for these loads.
+    const PackedHeader wh = *static_cast<const PackedHeader *>(a.w);
+    const PackedHeader xh = *a.xh;
 
-    const int nl = lane & 15, g = lane >> 4;
-    const int64_t rtA = rg * (kSkRows / kTileRows) + wave * 2;   // the wave's two row-tiles: rtA, rtA + 1
-    const int my_sel = nl >> 3;                        // which of the two this lane's weight row is in
-    const int64_t my_rt = rtA + my_sel;
-    const bool row_ok = my_rt < lw.n_rt;
-    const int slot0 = (nl & 7) * kTileBlocks + 2 * g;  // slots of blocks 2g, 2g+1 within the tile
-    const int spec_sel = lane >> 5, spec_e = lane & 31;
-    const bool spec_ok = rtA + spec_sel < lw.n_rt;
-
-    // Loads are unconditional (indices clamped into the buffer, results masked at
-    // use) so that the number of loads in flight is known at compile time and a
-    // consume step waits only for its own K-tile, not for the prefetches behind
-    // it.  Everything whose address does not depend on another load goes first.
-    const int64_t rt_ld = row_ok ? my_rt : 0;
-    const int64_t spec_rt_ld = spec_ok ? rtA + spec_sel : 0;
-    const uint64_t h_last = (uint64_t)lw.n_tiles * kTileSlots - 1;
-    uint64_t mcol[kSkMaxCols];   // mask word of the lane's own tile, per K-tile
-    uint32_t tcol[kSkMaxCols];   // plane-H offset of the lane's speculative tile, per K-tile
+    // ---- activations: 16 MT rows x (ncols * 128) halves, straight into LDS; one wave-load fills
+    // 1 KB = half a row.  Chunks past the K range re-read the row's first chunk (never used).
+    {
+        const char *xg = reinterpret_cast<const char *>(a.x16) + c0 * (kTileK * 2);
 #pragma unroll
-    for (int c = 0; c < kSkMaxCols; ++c) {
-        const int cc = c < ncols ? c : ncols - 1;
-        mcol[c] = W.M[rt_ld * lw.n_kt + c0 + cc];
-        tcol[c] = W.T[spec_rt_ld * lw.n_kt + c0 + cc];
+        for (int u = 0; u < 32 * MT / kWaves; ++u) {
+            const int id = wave + kWaves * u, r = id >> 1, h = id & 1;
+            const int chunk = h * 64 + lane;
+            const int src_chunk = chunk < ncols * (kTileK / 8) ? chunk : 0;
+            __builtin_amdgcn_global_load_lds((global_void_t *)(xg + (int64_t)r * a.ld16 * 2 + src_chunk * 16),
+                                             (lds_void_t *)&xs[r][h * 512], 16, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep these loads ahead of all others (see the barrier below)
     }
+
+    // ---- weights.  Planes L, S, M, T have fixed extents; plane H ends where the header says (a
+    // compact tensor may live in a buffer of exactly bytes_used bytes).
+    const __amdgpu_buffer_rsrc_t wbuf =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)(uint32_t)lw.off_H, kRsrcFlags);
+    const int nl = lane & 15, g = lane >> 4;
+    const int64_t rtA = rg * (kRows / kTileRows) + wave * 2;   // the wave's two row-tiles: rtA, rtA + 1
+    const int my_sel = nl >> 3;                        // which of the two this lane's weight row is in
+    const int slot0 = (nl & 7) * kTileBlocks + 2 * g;  // slots of blocks 2g, 2g+1 within the tile
+    const int spec_e = lane & 31;
+    const uint32_t tile0 = (uint32_t)((rtA + my_sel) * lw.n_kt + c0);
+    const uint32_t voff_L = (uint32_t)lw.off_L + (tile0 * kTileSlots + slot0) * 8u;
+    const uint32_t voff_S = (uint32_t)lw.off_S + tile0 * kTileSlots + slot0;
+    // Per-tile words (mask, plane-H offset) of the wave's 2 x 8 tiles: fetched one tile per lane and
+    // parked in LDS, where the loop picks the byte / word it needs with one read.
+    const uint32_t mt_tile = (uint32_t)((rtA + ((lane >> 3) & 1)) * lw.n_kt + c0 + (lane & 7));
+    const uint2 mvec = ld64(wbuf, (uint32_t)lw.off_M + mt_tile * 8u);
+    const uint32_t tvec = ld32(wbuf, (uint32_t)lw.off_T + mt_tile * 4u);
+
     auto issue_ls = [&](int c, SkinnyStage &st) {
-        const int cc = c < ncols ? c : ncols - 1;
-        const int64_t tile = rt_ld * lw.n_kt + c0 + cc;
-        st.l = *reinterpret_cast<const uint4 *>(&W.L[tile * kTileSlots + slot0]);
-        st.s = *reinterpret_cast<const uint16_t *>(&W.S[tile * kTileSlots + slot0]);
-    };
-    auto issue_h = [&](int c, SkinnyStage &st) {
-        const uint64_t hidx = (uint64_t)tcol[c] + spec_e;
-        st.h = W.H[hidx < h_last ? hidx : h_last];
+        // the K-tile displacement is uniform: it travels in the scalar offset, not through the vector ALU
+        st.l = ld128(wbuf, voff_L, (uint32_t)(kTileSlots * 8) * c);
+        st.s = ld16(wbuf, voff_S, (uint32_t)kTileSlots * c);
     };
     SkinnyStage ring[kSkPrefetch];
 #pragma unroll
     for (int p = 0; p < kSkPrefetch; ++p) issue_ls(p, ring[p]);
 
-    // activations of this K range: packed tiles (8 rows x 128 K, one block per lane) decoded straight
-    // into LDS; 2 MT row-tiles x ncols K-tiles, spread over the 4 waves
-    {
-#pragma unroll
-        for (int p = 0; p < kSkPrefetch; ++p) issue_h(p, ring[p]);
-        const bool x_ok = xh.magic == kMagic && xh.rows == lx.rows && xh.K == lx.K;
-        const int n_xt = 2 * MT * ncols;
-        for (int i = wave; i < n_xt; i += 4) {
-            const int xrt = i / ncols, xc = i % ncols;
-            half2_t vals[8];
-            if (xrt < lx.n_rt && x_ok) {
-                decode_slot(X, (int64_t)xrt * lx.n_kt + c0 + xc, lane, vals);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) vals[j] = half2_t{(_Float16)0.0f, (_Float16)0.0f};
-            }
-            const uint32_t *w = reinterpret_cast<const uint32_t *>(vals);
-            uint4 *dst = reinterpret_cast<uint4 *>(&xs[xrt * kTileRows + (lane >> 3)][xc * kTileK + (lane & 7) * kBlock]);
-            dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-            dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-        }
+    const bool w_ok = wh.magic == kMagic && wh.rows == lw.rows && wh.K == lw.K;
+    const bool x_ok = xh.magic == kMagic && xh.rows == a.lx.rows && xh.K == a.lx.K;
+    const uint32_t w_used = w_ok ? (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)wh.bytes_used) : 0u;
+    const __amdgpu_buffer_rsrc_t hbuf =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)w_used, kRsrcFlags);
+    // does any of the wave's tiles hold more FP8 blocks than the speculative window covers?
+    const bool any_far = __builtin_amdgcn_ballot_w64(__popc(mvec.x) + __popc(mvec.y) > kSkSpec) != 0ull;
+    if (lane < 16) {
+        m_lds[wave][lane] = mvec;
+        t_lds[wave][lane] = tvec;
     }
+    // (written and read by the same wave, LDS operations of a wave execute in order: no barrier needed)
+    const uint8_t *m_byte = reinterpret_cast<const uint8_t *>(&m_lds[wave][my_sel * 8]) + (nl & 7);
+    const uint32_t *t_word = &t_lds[wave][(lane >> 5) * 8];
+    // the upper halves of FP8 blocks: 32 consecutive plane-H entries of each of the wave's two tiles
+    auto issue_h = [&](int c, SkinnyStage &st) {
+        st.h = ld64(hbuf, (uint32_t)lw.off_H + (t_word[c & 7] + spec_e) * 8u);
+    };
+#pragma unroll
+    for (int p = 0; p < kSkPrefetch; ++p) issue_h(p, ring[p]);
+
+    // The activation loads were issued before the per-tile words that issue_h has just waited for, and
+    // loads complete in order: they have landed.
     __syncthreads();
 
     float4_t acc[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) acc[i] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
+    const _Float16 *xrow = &xs[nl][32 * g];
     auto consume = [&](int c, const SkinnyStage &st) {
-        if (c >= ncols) return;
-        const uint64_t m = row_ok ? mcol[c] : 0ull;
-        const uint4 lv = row_ok ? st.l : make_uint4(0, 0, 0, 0);
-        const uint32_t sv = row_ok ? st.s : 0u;
-        const uint32_t s0 = sv & 0xFFu, s1 = (sv >> 8) & 0xFFu;
-        const bool hi0 = (m >> slot0) & 1ull, hi1 = (m >> (slot0 + 1)) & 1ull;
-        // upper halves of FP8 blocks: entry s of the lane's tile sits in lane 32 * my_sel + s
+        const uint32_t mbits = (uint32_t)m_byte[c * 8] >> (2 * g);   // bits 0, 1: blocks 2g, 2g+1 are FP8
+        const uint32_t s0 = st.s & 0xFFu, s1 = (st.s >> 8) & 0xFFu;
+        const bool hi0 = mbits & 1u, hi1 = mbits & 2u;
+        // entry s of the lane's tile was fetched by lane 32 * my_sel + s
+        const int a0 = (my_sel * kSkSpec + (int)(s0 & (kSkSpec - 1))) << 2;
+        const int a1 = (my_sel * kSkSpec + (int)(s1 & (kSkSpec - 1))) << 2;
         uint2 up0, up1;
-        {
-            const int a0 = (my_sel * kSkSpec + (int)(s0 & (kSkSpec - 1))) << 2;
-            const int a1 = (my_sel * kSkSpec + (int)(s1 & (kSkSpec - 1))) << 2;
-            up0.x = __builtin_amdgcn_ds_bpermute(a0, st.h.x);
-            up0.y = __builtin_amdgcn_ds_bpermute(a0, st.h.y);
-            up1.x = __builtin_amdgcn_ds_bpermute(a1, st.h.x);
-            up1.y = __builtin_amdgcn_ds_bpermute(a1, st.h.y);
-            // Tiles with more FP8 blocks than the speculative window: fetch directly.
-            // Rare; the wait sits inside the branch so that the common path keeps
-            // counting only its own prefetches.
+        up0.x = __builtin_amdgcn_ds_bpermute(a0, st.h.x);
+        up0.y = __builtin_amdgcn_ds_bpermute(a0, st.h.y);
+        up1.x = __builtin_amdgcn_ds_bpermute(a1, st.h.x);
+        up1.y = __builtin_amdgcn_ds_bpermute(a1, st.h.y);
+        // Tiles with more FP8 blocks than the speculative window: fetch directly.  Rare; the wait sits
+        // inside the branch so that the common path keeps counting only its own prefetches.
+        if (any_far) {
             const bool far0 = hi0 && s0 >= (uint32_t)kSkSpec, far1 = hi1 && s1 >= (uint32_t)kSkSpec;
-            if (__builtin_amdgcn_ballot_w64(far0 || far1) != 0ull) {
-                const uint32_t tA = __builtin_amdgcn_readlane(tcol[c], 0), tB = __builtin_amdgcn_readlane(tcol[c], 32);
-                const uint64_t my_t = my_sel ? tB : tA;
-                if (far0) up0 = W.H[my_t + s0];
-                if (far1) up1 = W.H[my_t + s1];
-                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-            }
+            const uint32_t my_t = t_lds[wave][my_sel * 8 + c];
+            if (far0) up0 = ld64(hbuf, (uint32_t)lw.off_H + (my_t + s0) * 8u);
+            if (far1) up1 = ld64(hbuf, (uint32_t)lw.off_H + (my_t + s1) * 8u);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         }
         half2_t b[16];   // b[4 j + i]: halves 2i, 2i+1 of MFMA j's operand
-        if (hi0) {
-            b[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.x, 1.0f, false);
-            b[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.x, 1.0f, true);
-            b[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.y, 1.0f, false);
-            b[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.y, 1.0f, true);
-            b[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up0.x, 1.0f, false);
-            b[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up0.x, 1.0f, true);
-            b[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up0.y, 1.0f, false);
-            b[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up0.y, 1.0f, true);
-        } else {
-            const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(s0 | (s0 << 8), 1.0f, false);
-            b[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.x, 1.0f, 0) * s;
-            b[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.x, 1.0f, 1) * s;
-            b[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.x, 1.0f, 2) * s;
-            b[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.x, 1.0f, 3) * s;
-            b[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.y, 1.0f, 0) * s;
-            b[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.y, 1.0f, 1) * s;
-            b[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.y, 1.0f, 2) * s;
-            b[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.y, 1.0f, 3) * s;
-        }
-        if (hi1) {
-            b[8] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.z, 1.0f, false);
-            b[9] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.z, 1.0f, true);
-            b[10] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.w, 1.0f, false);
-            b[11] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lv.w, 1.0f, true);
-            b[12] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up1.x, 1.0f, false);
-            b[13] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up1.x, 1.0f, true);
-            b[14] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up1.y, 1.0f, false);
-            b[15] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(up1.y, 1.0f, true);
-        } else {
-            const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(s1 | (s1 << 8), 1.0f, false);
-            b[8] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.z, 1.0f, 0) * s;
-            b[9] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.z, 1.0f, 1) * s;
-            b[10] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.z, 1.0f, 2) * s;
-            b[11] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.z, 1.0f, 3) * s;
-            b[12] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.w, 1.0f, 0) * s;
-            b[13] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.w, 1.0f, 1) * s;
-            b[14] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.w, 1.0f, 2) * s;
-            b[15] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lv.w, 1.0f, 3) * s;
-        }
+        decode_block(make_uint2(st.l.x, st.l.y), s0, hi0, up0, reinterpret_cast<half2_t(&)[8]>(b[0]));
+        decode_block(make_uint2(st.l.z, st.l.w), s1, hi1, up1, reinterpret_cast<half2_t(&)[8]>(b[8]));
         const half8_t *bv = reinterpret_cast<const half8_t *>(b);
+        const _Float16 *xc = xrow + c * kTileK;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const half8_t a = *reinterpret_cast<const half8_t *>(&xs[mt * 16 + nl][c * kTileK + 32 * g + 8 * j]);
-                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bv[j], acc[mt], 0, 0, 0);
+                const half8_t af = *reinterpret_cast<const half8_t *>(xc + mt * 16 * kXRow + 8 * j);
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bv[j], acc[mt], 0, 0, 0);
             }
         }
     };
-
+    // The ring is indexed statically (the loop body covers one turn of it): a stage's registers are
+    // the targets of loads in flight and must not be copied.  Tiles past the K range read other bytes
+    // of the buffer (or zeros) that are never consumed.
+#pragma unroll 1
+    for (int c0r = 0; c0r < ncols; c0r += kSkPrefetch) {
 #pragma unroll
-    for (int c = 0; c < kSkMaxCols; ++c) {
-        consume(c, ring[c % kSkPrefetch]);
-        if (c + kSkPrefetch < kSkMaxCols) {
-            issue_ls(c + kSkPrefetch, ring[c % kSkPrefetch]);
-            issue_h(c + kSkPrefetch, ring[c % kSkPrefetch]);
+        for (int p = 0; p < kSkPrefetch; ++p) {
+            const int c = c0r + p;
+            if (c < ncols) consume(c, ring[p]);
+            issue_ls(c + kSkPrefetch, ring[p]);
+            issue_h(c + kSkPrefetch, ring[p]);
         }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the prefetches issued past the K range
 
+    float *const Y = a.Y;
+    const int64_t ldy = a.ldy, M = a.M, N = a.N;
     // acc[mt][r] = partial Y[m = 16 mt + 4 (lane / 16) + r][n = 64 rg + 16 wave + lane % 16]
-    const bool w_ok = wh.magic == kMagic && wh.rows == lw.rows && wh.K == lw.K;
-    const float ss = w_ok ? xh.tensor_scale * wh.tensor_scale : 0.0f;
-    const int n_local = wave * 16 + nl;
+    // operands whose headers do not match the call's shapes count as zeros
+    const bool ok = w_ok && x_ok;
+    const float ss = xh.tensor_scale * wh.tensor_scale;
+    const int64_t n = rg * kRows + wave * 16 + nl;
     if (ksplit == 1) {
-        const int64_t n = rg * kSkRows + n_local;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int64_t m = mt * 16 + 4 * g + r;
-                if (m < M && n < N) Y[m * ldy + n] = acc[mt][r] * ss;
+                if (m < M && n < N) Y[m * ldy + n] = ok ? acc[mt][r] * ss : 0.0f;
             }
         return;
     }
-    // Partial tile layout: [n_local (64)][m (16 MT)], so a lane's four accumulators of one MFMA tile
-    // (rows 4g .. 4g+3 of column n_local) are 16 contiguous bytes.  Partials and the arrival counter
-    // cross XCDs: they are written and read with system-coherent vector accesses (sc0 sc1), which
-    // bypass the per-XCD L2, and the stores are waited for before the counter is bumped, so no cache
-    // write-back or invalidate is needed.
-    constexpr uint32_t kTileBytes32 = kSkRows * (16 * MT) * 4;   // bytes of one partial tile
+    // K ranges are combined per wave (16 weight rows), without workgroup barriers.  Partial layout:
+    // [workgroup][wave][mt][lane] vectors of 16 bytes, a lane's four accumulators of one MFMA tile.
+    // Partials and counters cross XCDs: they are written and read with system-coherent vector
+    // accesses (sc0 sc1), which bypass the per-XCD L2; a wave's stores are complete before it bumps
+    // the counter, so the wave that observes the last arrival reads complete partials.  It adds them
+    // in K order -- the result does not depend on which wave came last.
+    constexpr uint32_t kWaveBytes = 64 * 16 * MT;                 // one wave's partial
     const __amdgpu_buffer_rsrc_t pbuf =
-        __builtin_amdgcn_make_buffer_rsrc(partial, 0, (int)partial_bytes, 0x00020000);
-    const uint32_t mine = (uint32_t)blockIdx.x * kTileBytes32;
+        __builtin_amdgcn_make_buffer_rsrc(a.partial, 0, (int)a.partial_bytes, kRsrcFlags);
+    const uint32_t mine = ((uint32_t)blockIdx.x * kWaves + wave) * kWaveBytes + lane * 16u;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) store_coherent16(pbuf, mine + mt * 1024u, acc[mt]);
+    __builtin_amdgcn_s_waitcnt(0);
+    uint32_t before = 0;
+    if (lane == 0)
+        before = __hip_atomic_fetch_add(&a.counters[rg * kWaves + wave], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    before = __builtin_amdgcn_readfirstlane(before);
+    if (before != (uint32_t)(ksplit - 1)) return;
+    const uint32_t first = ((uint32_t)(rg * ksplit) * kWaves + wave) * kWaveBytes + lane * 16u;
+    float4_t sum[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) sum[mt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int k0 = 0; k0 < ksplit; k0 += kSkSumPass) {
+        float4_t part[kSkSumPass][MT];
+#pragma unroll
+        for (int k = 0; k < kSkSumPass; ++k) {
+            const int kk = k0 + k < ksplit ? k0 + k : ksplit - 1;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                part[k][mt] = load_coherent16(pbuf, first + (uint32_t)kk * (kWaves * kWaveBytes) + mt * 1024u);
+        }
+#pragma unroll
+        for (int k = 0; k < kSkSumPass; ++k)
+            if (k0 + k < ksplit) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) sum[mt] += part[k][mt];
+            }
+    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-        store_coherent16(pbuf, mine + (uint32_t)(n_local * (16 * MT) + mt * 16 + 4 * g) * 4u, acc[mt]);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0) arrival = arrive(&counters[rg], epoch);
-    __syncthreads();
-    if (arrival != (uint32_t)(ksplit - 1)) return;
-    // last workgroup of this row group: add the partials in K order, 4 rows of one column per thread
-    const uint32_t first = (uint32_t)(rg * ksplit) * kTileBytes32;
-    constexpr int kVecs = kSkRows * (16 * MT) / 4;   // 16-byte vectors per partial tile
-    for (int i = tid; i < kVecs; i += 256) {
-        float4_t sum = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-        for (int k0 = 0; k0 < ksplit; k0 += kSkSumPass) {
-            float4_t part[kSkSumPass];
 #pragma unroll
-            for (int k = 0; k < kSkSumPass; ++k) {
-                const int kk = k0 + k < ksplit ? k0 + k : ksplit - 1;
-                part[k] = load_coherent16(pbuf, first + (uint32_t)kk * kTileBytes32 + (uint32_t)i * 16u);
-            }
-#pragma unroll
-            for (int k = 0; k < kSkSumPass; ++k)
-                if (k0 + k < ksplit) sum += part[k];
+        for (int r = 0; r < 4; ++r) {
+            const int64_t m = mt * 16 + 4 * g + r;
+            if (m < M && n < N) Y[m * ldy + n] = ok ? sum[mt][r] * ss : 0.0f;
         }
-        const int64_t n = rg * kSkRows + i / (4 * MT);
-        const int64_t m0 = (i % (4 * MT)) * 4;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if (m0 + r < M && n < N) Y[(m0 + r) * ldy + n] = sum[r] * ss;
-    }
 }
 
 // ---- host side ----
 
 struct SkinnyPlan {
-    int mt, cols_per_wg, ksplit;
+    int mt, waves, cols_per_wg, ksplit;
     int64_t row_groups;
     size_t off_partial, off_counters, total;
 };
@@ -315,9 +324,14 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     SkinnyPlan p;
     const PackedLayout lw = make_layout(N, K);
     p.mt = M <= 16 ? 1 : 2;
-    p.row_groups = (N + kSkRows - 1) / kSkRows;
+    // 17..32 rows of X need twice the LDS per workgroup: 8 waves share it, so that every workgroup of
+    // the launch is still resident at once
+    p.waves = p.mt == 1 ? 4 : 8;
+    const int64_t rows_per_wg = 16 * p.waves;
+    p.row_groups = (N + rows_per_wg - 1) / rows_per_wg;
     // about three workgroups per CU, at most 8 K-tiles each
-    int64_t want = (768 + p.row_groups - 1) / p.row_groups;
+    const int64_t target_wgs = p.mt == 1 ? 768 : 384;
+    int64_t want = (target_wgs + p.row_groups - 1) / p.row_groups;
     int max_cols = kSkMaxCols;
     const int64_t need = (lw.n_kt + max_cols - 1) / max_cols;
     if (want < need) want = need;
@@ -327,41 +341,55 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     p.cols_per_wg = (int)((lw.n_kt + want - 1) / want);
     p.ksplit = (int)((lw.n_kt + p.cols_per_wg - 1) / p.cols_per_wg);
     p.off_partial = 0;
-    p.off_counters = (size_t)align_up((uint64_t)p.row_groups * p.ksplit * (16 * p.mt) * kSkRows * 4, 256);
-    p.total = p.off_counters + (size_t)align_up((uint64_t)p.row_groups * 8, 256);
+    p.off_counters = (size_t)align_up((uint64_t)p.row_groups * p.ksplit * (16 * p.mt) * rows_per_wg * 4, 256);
+    p.total = p.off_counters + (size_t)align_up((uint64_t)p.row_groups * p.waves * sizeof(uint32_t), 256);
     return p;
 }
 
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return skinny_plan(M, N, K).total; }
 
-// A fresh 56-bit tag per call for the arrival counters (see arrive()).
-static unsigned long long next_epoch()
+bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K)
 {
-    static std::atomic<unsigned long long> counter{[] {
-        std::random_device rd;
-        return ((unsigned long long)rd() << 32) ^ rd() ^ (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
-    }()};
-    return counter.fetch_add(1) & ((1ull << 56) - 1);
+    // buffer loads address the packed tensors with 32-bit offsets
+    constexpr uint64_t kLimit = 0xFFFFFF00ull;
+    return M <= kSkinnyMaxRows && make_layout(N, K).total_bytes < kLimit && make_layout(M, K).total_bytes < kLimit;
 }
 
-fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
-                          int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st)
+int64_t gemm_skinny_x16_rows(int64_t M) { return M <= 16 ? 16 : 32; }
+
+// The arrival counters of a call must be zero when the kernel starts: the caller clears
+// gemm_skinny_counters(...) words in the kernel that prepares x16 (same stream).
+SkinnyCounters gemm_skinny_counters(int64_t M, int64_t N, int64_t K, void *workspace)
 {
     const SkinnyPlan p = skinny_plan(M, N, K);
+    return SkinnyCounters{reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + p.off_counters),
+                          p.ksplit > 1 ? p.row_groups * p.waves : 0};
+}
+
+fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const _Float16 *x16, int64_t ld16,
+                          const void *w, const PackedLayout &lw, int64_t M, int64_t N, int64_t K, float *Y,
+                          int64_t ldy, void *workspace, hipStream_t st)
+{
+    if (!gemm_skinny_applies(M, N, K)) return FGMP_ERR_UNSUPPORTED;
+    const SkinnyPlan p = skinny_plan(M, N, K);
     char *ws = static_cast<char *>(workspace);
-    float *partial = reinterpret_cast<float *>(ws + p.off_partial);
-    unsigned long long *counters = reinterpret_cast<unsigned long long *>(ws + p.off_counters);
     const size_t partial_bytes = p.off_counters - p.off_partial;
     if (p.row_groups * p.ksplit > 0x7FFFFFFF || partial_bytes > 0x7FFFFFFFu || p.ksplit > 255)
         return FGMP_ERR_UNSUPPORTED;
-    const unsigned long long epoch = next_epoch();
+    if (!xh || !x16 || ld16 < lx.n_kt * kTileK || (uintptr_t)x16 % 16 != 0 || (ld16 * 2) % 16 != 0)
+        return FGMP_ERR_BAD_SHAPE;
+    SkinnyArgs a;
+    a.w = w; a.lw = lw;
+    a.xh = xh; a.lx = lx;
+    a.x16 = x16; a.ld16 = ld16;
+    a.cols_per_wg = p.cols_per_wg; a.ksplit = p.ksplit;
+    a.partial = reinterpret_cast<float *>(ws + p.off_partial);
+    a.partial_bytes = (uint32_t)partial_bytes;
+    a.counters = reinterpret_cast<uint32_t *>(ws + p.off_counters);
+    a.Y = Y; a.ldy = ldy; a.M = M; a.N = N;
     const dim3 grid((unsigned)(p.row_groups * p.ksplit));
-    if (p.mt == 1)
-        hipLaunchKernelGGL((gemm_skinny_kernel<1>), grid, dim3(256), 0, st, W, lw, X, lx, p.cols_per_wg, p.ksplit,
-                           partial, (uint32_t)partial_bytes, counters, epoch, Y, ldy, M, N);
-    else
-        hipLaunchKernelGGL((gemm_skinny_kernel<2>), grid, dim3(256), 0, st, W, lw, X, lx, p.cols_per_wg, p.ksplit,
-                           partial, (uint32_t)partial_bytes, counters, epoch, Y, ldy, M, N);
+    if (p.mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<2, 8>), grid, dim3(512), 0, st, a);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }
 

@@ -21,7 +21,8 @@ constexpr bool kUseHwCvt = FGMP_HW_CVT != 0;
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
-                              _Float16 *x16 = nullptr, int64_t ld16 = 0);
+                              _Float16 *x16 = nullptr, int64_t ld16 = 0, uint32_t *zero = nullptr,
+                              int64_t zero_n = 0);
 fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
                             uint8_t *mask, hipStream_t st);
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
@@ -31,9 +32,22 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
                          float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
                          void *workspace, size_t workspace_bytes, hipStream_t st);
+// Decode shapes (few rows of X): weight-streaming kernel.  X is given as FP16 values (`x16`,
+// gemm_skinny_x16_rows(M) rows of ld16 halves; rows from M rounded up to 8 on are never used for a
+// stored output) plus the header of its packed form.
+constexpr int64_t kSkinnyMaxRows = 32;
+bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K);
+int64_t gemm_skinny_x16_rows(int64_t M);
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K);
-fgmp_status_t gemm_skinny(const PackedView &X, const PackedLayout &lx, const PackedView &W, const PackedLayout &lw,
-                          int64_t M, int64_t N, int64_t K, float *Y, int64_t ldy, void *workspace, hipStream_t st);
+// arrival counters inside a skinny workspace; the kernel that prepares x16 must zero them
+struct SkinnyCounters {
+    uint32_t *ptr;
+    int64_t n;
+};
+SkinnyCounters gemm_skinny_counters(int64_t M, int64_t N, int64_t K, void *workspace);
+fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const _Float16 *x16, int64_t ld16,
+                          const void *w, const PackedLayout &lw, int64_t M, int64_t N, int64_t K, float *Y,
+                          int64_t ldy, void *workspace, hipStream_t st);
 // packed -> zero-padded dense FP16 [8 n_rt_pad][ld]; one launch decodes one or two tensors and
 // can clear `zero_n` 32-bit counters
 struct DecodeJob {

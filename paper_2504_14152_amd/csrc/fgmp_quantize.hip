@@ -44,6 +44,8 @@ struct QuantParams {
     uint32_t compact;
     _Float16 *x16;         // kModeF16: dequantized values (without the tensor scale), [8 n_rt][ld16]
     int64_t ld16;
+    uint32_t *zero;        // words cleared by the first workgroup (counters of the kernel that follows)
+    int zero_n;
 };
 
 // kModeF16 writes, instead of the packed planes, the FP16 value of every stored
@@ -157,6 +159,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
         if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && p.out.hdr != nullptr)
             write_header(p.out.hdr, p.layout, p.S, p.compact);
     }
+    if (blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i < p.zero_n; i += 256) p.zero[i] = 0u;
 
     const int64_t rt0 = (int64_t)blockIdx.y * p.rt_per_wave * 4 + wave;
     // out-of-range lanes read a valid address (their own K-tile's first block of row 0) and are masked
@@ -414,7 +418,7 @@ static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipS
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
-                              _Float16 *x16, int64_t ld16)
+                              _Float16 *x16, int64_t ld16, uint32_t *zero, int64_t zero_n)
 {
     if (!X || !fisher || (!packed && !x16)) return FGMP_ERR_INVALID_ARG;
     if (rows <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
@@ -454,6 +458,8 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
     p.layout = l;
     p.compact = compact ? 1u : 0u;
     p.x16 = x16; p.ld16 = ld16;
+    if (zero_n < 0 || zero_n > 0x7FFFFFFF || (zero_n > 0 && !zero)) return FGMP_ERR_INVALID_ARG;
+    p.zero = zero; p.zero_n = (int)zero_n;
     if (x16 != nullptr) {
         p.mode = kModeF16;
         if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);
