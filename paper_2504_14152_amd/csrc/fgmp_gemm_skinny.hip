@@ -13,9 +13,11 @@
 // 1 KB of consecutive plane-L bytes -- and decodes them into the B operands of
 // four 16x16x32 MFMAs; MFMA j therefore reduces over the K elements
 // 32 g + 8 j .. 32 g + 8 j + 7 (g = 0..3) of the tile, and the A operand is
-// read from LDS with the same assignment.  The FP8 blocks' upper halves (plane
-// H) of a tile are fetched speculatively, 32 entries per tile per wave, and
-// handed to the lane that needs them with ds_bpermute.
+// read from LDS with the same assignment.  Only plane L is streamed tile by
+// tile; the small planes of a wave's 2 x 8 tiles -- scale bytes, mask words and
+// the FP8 blocks' upper halves (plane H, contiguous for consecutive K-tiles of
+// a compact tensor) -- are fetched in bulk at the start, with full-width loads,
+// and parked in LDS, where each lane picks its bytes per tile.
 //
 // The kernel is bound by vector-ALU issue, not by HBM, so address arithmetic is
 // kept off the vector unit: every access to the packed tensors is a buffer load
@@ -23,6 +25,8 @@
 // immediate.  The buffer range check also makes every load safe without a
 // select: tiles past the K range or rows past the tensor read other tiles'
 // bytes or zeros, and their results are never stored.
+#include <cstddef>
+
 #include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
@@ -31,10 +35,13 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSkMaxCols = 8;     // K-tiles per workgroup
+// K-tiles per workgroup and plane-H entries staged per row-tile and K range (FP8 blocks beyond fetch
+// their entry directly).  Sized by LDS: every workgroup of a launch should be resident at once (3 per
+// CU with 4 waves and up to 16 rows of X, 2 per CU with 8 waves and 17..32 rows).
+constexpr int skinny_max_cols(int mt) { return mt == 1 ? 8 : 7; }
+constexpr int skinny_h_window(int mt) { return mt == 1 ? 192 : 64; }
 constexpr int kSkPrefetch = 4;    // plane-L/S K-tiles in flight per wave
 constexpr int kSkXPad = 8;        // halves of padding per LDS activation row
-constexpr int kSkSpec = 32;       // plane-H entries fetched speculatively per tile
 
 constexpr int kSkSumPass = 4;     // partial tiles summed per pass (their loads are in flight together)
 constexpr int kSkMaxSplit = 16;   // most K ranges per row group the planner asks for
@@ -77,25 +84,27 @@ __device__ __forceinline__ uint32_t ld8(__amdgpu_buffer_rsrc_t b, uint32_t off)
     return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(b, (int)off, 0, 0);
 }
 
+static_assert(offsetof(PackedHeader, magic) == 0 && offsetof(PackedHeader, rows) == 8 && offsetof(PackedHeader, K) == 16 &&
+                  offsetof(PackedHeader, tensor_scale) == 24 && offsetof(PackedHeader, h_entries) == 72 &&
+                  offsetof(PackedHeader, bytes_used) == 80,
+              "the kernel reads these header fields by byte offset");
+
 struct SkinnyStage {
     uint4 l;       // blocks 2g, 2g+1 of this lane's row
-    uint32_t s;    // their two scale-or-index bytes
-    uint2 h;       // speculative plane-H entry (lane & 31) of tile (lane >> 5)
 };
 
 struct SkinnyArgs {
     const void *w;            // packed weights (header first)
-    PackedLayout lw;
     const PackedHeader *xh;   // header of the activations (tensor scale, shape check)
-    PackedLayout lx;
     const _Float16 *x16;      // activations as FP16 values, [>= 16 MT rows][ld16]
-    int64_t ld16;
-    int cols_per_wg, ksplit;
-    float *partial;
-    uint32_t partial_bytes;
-    uint32_t *counters;       // one per (row group, wave), zeroed by the kernel that prepares x16
     float *Y;
-    int64_t ldy, M, N;
+    float *partial;
+    uint32_t *counters;       // one per (row group, wave), zeroed by the kernel that prepares x16
+    int64_t ld16, ldy, M, N;
+    int64_t w_rows, w_K, x_rows, x_K;                          // the shapes the headers must state
+    uint32_t off_L, off_S, off_M, off_T, off_H, n_tiles;       // layout of the packed weights
+    uint32_t partial_bytes;
+    int n_kt, cols_per_wg, ksplit;
 };
 
 // The code is kept small on purpose (a rolled K-tile loop with a rotating register ring instead of a
@@ -107,89 +116,126 @@ template <int MT, int kWaves>
 __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
 {
     constexpr int kRows = 16 * kWaves;   // weight rows per workgroup
+    constexpr int kSkMaxCols = skinny_max_cols(MT), kSkHWin = skinny_h_window(MT);
     constexpr int kXRow = kSkMaxCols * kTileK + kSkXPad;
     __shared__ __attribute__((aligned(1024))) _Float16 xs[16 * MT][kXRow];
-    __shared__ uint2 m_lds[kWaves][16];       // per wave: mask words, [sel][K-tile]
-    __shared__ uint32_t t_lds[kWaves][16];    // per wave: plane-H offsets, [sel][K-tile]
+    // per wave (sel = which of its two row-tiles):
+    __shared__ uint2 m_lds[kWaves][16];                       // mask words, [sel][K-tile]
+    __shared__ uint32_t t_lds[kWaves][16];                    // plane-H offsets relative to the K range's first, [sel][K-tile]
+    __shared__ __attribute__((aligned(16))) uint8_t s_lds[kWaves][2][8 * kTileSlots];   // plane S, [sel][K-tile][slot] (always 8 tiles' worth is loaded)
+    __shared__ __attribute__((aligned(16))) uint2 h_lds[kWaves][2][kSkHWin];                     // plane H window, [sel][entry]
 
-    const PackedLayout &lw = a.lw;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ksplit = a.ksplit;
     const int64_t rg = blockIdx.x / ksplit;
     const int ks = blockIdx.x % ksplit;
-    const int64_t c0 = (int64_t)ks * a.cols_per_wg;
-    const int ncols = (int)((lw.n_kt - c0 < a.cols_per_wg) ? lw.n_kt - c0 : a.cols_per_wg);
-    // Headers: only the FP8 upper-half fetches (which come a round trip later anyway) and the final
-    // scaling depend on them; the plane-L stream starts without waiting for these loads.
-    const PackedHeader wh = *static_cast<const PackedHeader *>(a.w);
-    const PackedHeader xh = *a.xh;
+    const int c0 = ks * a.cols_per_wg;
+    const int ncols = (a.n_kt - c0 < a.cols_per_wg) ? a.n_kt - c0 : a.cols_per_wg;
 
-    // ---- activations: 16 MT rows x (ncols * 128) halves, straight into LDS; one wave-load fills
-    // 1 KB = half a row.  Chunks past the K range re-read the row's first chunk (never used).
-    {
-        const char *xg = reinterpret_cast<const char *>(a.x16) + c0 * (kTileK * 2);
-#pragma unroll
-        for (int u = 0; u < 32 * MT / kWaves; ++u) {
-            const int id = wave + kWaves * u, r = id >> 1, h = id & 1;
-            const int chunk = h * 64 + lane;
-            const int src_chunk = chunk < ncols * (kTileK / 8) ? chunk : 0;
-            __builtin_amdgcn_global_load_lds((global_void_t *)(xg + (int64_t)r * a.ld16 * 2 + src_chunk * 16),
-                                             (lds_void_t *)&xs[r][h * 512], 16, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep these loads ahead of all others (see the barrier below)
-    }
-
-    // ---- weights.  Planes L, S, M, T have fixed extents; plane H ends where the header says (a
-    // compact tensor may live in a buffer of exactly bytes_used bytes).
+    // Planes L, S, M, T have fixed extents; plane H ends where the header says (a compact tensor may
+    // live in a buffer of exactly bytes_used bytes).
     const __amdgpu_buffer_rsrc_t wbuf =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)(uint32_t)lw.off_H, kRsrcFlags);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)a.off_H, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t xhbuf =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<PackedHeader *>(a.xh), 0, (int)kHeaderBytes, kRsrcFlags);
     const int nl = lane & 15, g = lane >> 4;
-    const int64_t rtA = rg * (kRows / kTileRows) + wave * 2;   // the wave's two row-tiles: rtA, rtA + 1
+    const uint32_t rtA = (uint32_t)rg * (kRows / kTileRows) + wave * 2;   // the wave's two row-tiles: rtA, rtA + 1
     const int my_sel = nl >> 3;                        // which of the two this lane's weight row is in
     const int slot0 = (nl & 7) * kTileBlocks + 2 * g;  // slots of blocks 2g, 2g+1 within the tile
-    const int spec_e = lane & 31;
-    const uint32_t tile0 = (uint32_t)((rtA + my_sel) * lw.n_kt + c0);
-    const uint32_t voff_L = (uint32_t)lw.off_L + (tile0 * kTileSlots + slot0) * 8u;
-    const uint32_t voff_S = (uint32_t)lw.off_S + tile0 * kTileSlots + slot0;
-    // Per-tile words (mask, plane-H offset) of the wave's 2 x 8 tiles: fetched one tile per lane and
-    // parked in LDS, where the loop picks the byte / word it needs with one read.
-    const uint32_t mt_tile = (uint32_t)((rtA + ((lane >> 3) & 1)) * lw.n_kt + c0 + (lane & 7));
-    const uint2 mvec = ld64(wbuf, (uint32_t)lw.off_M + mt_tile * 8u);
-    const uint32_t tvec = ld32(wbuf, (uint32_t)lw.off_T + mt_tile * 4u);
+    const uint32_t tile0 = (rtA + my_sel) * a.n_kt + c0;
+    const uint32_t voff_L = a.off_L + (tile0 * kTileSlots + slot0) * 8u;
+    // Per-tile words (mask, plane-H offset) of the wave's 2 x 8 tiles, one tile per lane (lanes 0-15);
+    // lanes 16, 17 fetch the plane-H offset of the tile after the K range, i.e. where its entries end.
+    const int w_sel = (lane >> 3) & 1;
+    const uint32_t w_tile = (rtA + w_sel) * a.n_kt + c0 + (lane & 7);
+    const uint32_t end_tile = (rtA + (lane & 1)) * a.n_kt + c0 + ncols;
+    const uint32_t t_tile = lane < 16 ? w_tile : end_tile;
+    const uint32_t s_tile0 = (rtA + (lane >> 5)) * a.n_kt + c0;
+    const char *xg = reinterpret_cast<const char *>(a.x16) + (int64_t)c0 * (kTileK * 2);
+    const int64_t x_row_bytes = a.ld16 * 2;
+    // everything above only needs the kernel arguments; no load below waits for more than those
+    __builtin_amdgcn_sched_barrier(0);
 
-    auto issue_ls = [&](int c, SkinnyStage &st) {
+    // ---- activations: 16 MT rows x (ncols * 128) halves, straight into LDS; one wave-load fills
+    // 1 KB = half a row of 8 K-tiles.  Chunks past the K range re-read the row's first chunk (never used).
+#pragma unroll
+    for (int u = 0; u < 32 * MT / kWaves; ++u) {
+        const int id = wave + kWaves * u, r = id >> 1, h = id & 1;
+        const int chunk = h * 64 + lane;
+        const int src_chunk = chunk < ncols * (kTileK / 8) ? chunk : 0;
+        // (a row of fewer than 8 K-tiles ends inside the second wave-load: the lanes beyond it stay out)
+        if (chunk < kSkMaxCols * (kTileK / 8))
+            __builtin_amdgcn_global_load_lds((global_void_t *)(xg + r * x_row_bytes + src_chunk * 16),
+                                             (lds_void_t *)&xs[r][h * 512], 16, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // keep these loads ahead of all others (see the barrier below)
+
+    // ---- weights: the small planes of the 2 x 8 tiles in bulk, the headers, then the plane-L stream.
+    // The headers come through the vector memory path like everything else (every lane reads the same
+    // bytes), so that no wait for an earlier load also waits for them.
+    const uint2 mvec = ld64(wbuf, a.off_M + w_tile * 8u);
+    uint32_t tvec = ld32(wbuf, a.off_T + t_tile * 4u);
+    // plane S: 512 contiguous bytes per row-tile, one 16-byte load per lane
+    const uint4 svec = ld128(wbuf, a.off_S + s_tile0 * kTileSlots + (lane & 31) * 16u);
+    const uint4 wh0 = ld128(wbuf, 0), wh1 = ld128(wbuf, 16), wh2 = ld128(wbuf, 72);   // see PackedHeader
+    const uint4 xh0 = ld128(xhbuf, 0), xh1 = ld128(xhbuf, 16);
+
+    auto issue_l = [&](int c, SkinnyStage &st) {
         // the K-tile displacement is uniform: it travels in the scalar offset, not through the vector ALU
         st.l = ld128(wbuf, voff_L, (uint32_t)(kTileSlots * 8) * c);
-        st.s = ld16(wbuf, voff_S, (uint32_t)kTileSlots * c);
     };
     SkinnyStage ring[kSkPrefetch];
 #pragma unroll
-    for (int p = 0; p < kSkPrefetch; ++p) issue_ls(p, ring[p]);
+    for (int p = 0; p < kSkPrefetch; ++p) issue_l(p, ring[p]);
 
-    const bool w_ok = wh.magic == kMagic && wh.rows == lw.rows && wh.K == lw.K;
-    const bool x_ok = xh.magic == kMagic && xh.rows == a.lx.rows && xh.K == a.lx.K;
-    const uint32_t w_used = w_ok ? (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)wh.bytes_used) : 0u;
+    // header fields: magic at byte 0, rows at 8, K at 16, tensor_scale at 24, h_entries at 72, bytes_used at 80
+    auto hdr_ok = [](const uint4 &h0, const uint4 &h1, int64_t rows, int64_t K) {
+        return h0.x == kMagic && (((uint64_t)h0.w << 32) | h0.z) == (uint64_t)rows &&
+               (((uint64_t)h1.y << 32) | h1.x) == (uint64_t)K;
+    };
+    const bool w_ok = hdr_ok(wh0, wh1, a.w_rows, a.w_K);
+    const bool x_ok = hdr_ok(xh0, xh1, a.x_rows, a.x_K);
+    const float w_scale = __builtin_bit_cast(float, wh1.z), x_scale = __builtin_bit_cast(float, xh1.z);
+    const uint32_t w_h_entries = wh2.x;
+    const uint32_t w_used = w_ok ? (uint32_t)__builtin_amdgcn_readfirstlane((int)wh2.z) : 0u;
     const __amdgpu_buffer_rsrc_t hbuf =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)w_used, kRsrcFlags);
-    // does any of the wave's tiles hold more FP8 blocks than the speculative window covers?
-    const bool any_far = __builtin_amdgcn_ballot_w64(__popc(mvec.x) + __popc(mvec.y) > kSkSpec) != 0ull;
+
+    // Plane H: the entries of the K range's tiles of one row-tile are contiguous, from the first tile's
+    // offset to the offset of the tile after the range (the plane's end for the tensor's last tile).
+    if (lane >= 16 && end_tile >= a.n_tiles) tvec = w_h_entries;
+    const uint32_t startA = __builtin_amdgcn_readlane(tvec, 0), startB = __builtin_amdgcn_readlane(tvec, 8);
+    const uint32_t endA = __builtin_amdgcn_readlane(tvec, 16), endB = __builtin_amdgcn_readlane(tvec, 17);
+    const uint32_t needA = endA - startA, needB = endB - startB;       // entries (garbage rows: any value)
+    // any FP8 block of this wave beyond the staged window?  (then those blocks fetch their entry directly)
+    const bool any_far = needA > (uint32_t)kSkHWin || needB > (uint32_t)kSkHWin;
+    {
+        // 128 entries (1 KB) per wave-load and row-tile; as many loads as the fuller row-tile needs
+        const uint32_t need = needA > needB ? needA : needB;
+        const uint32_t my_start = (lane >> 5) ? startB : startA;   // lanes 0-31: row-tile A, 32-63: row-tile B
+#pragma unroll
+        for (int u = 0; u < kSkHWin / 64; ++u) {
+            if ((uint32_t)(64 * u) < need) {
+                const uint32_t e = 64u * u + 2u * (lane & 31);
+                const uint4 hv = ld128(hbuf, a.off_H + (my_start + e) * 8u);
+                *reinterpret_cast<uint4 *>(&h_lds[wave][lane >> 5][e]) = hv;
+            }
+        }
+    }
     if (lane < 16) {
         m_lds[wave][lane] = mvec;
-        t_lds[wave][lane] = tvec;
+        t_lds[wave][lane] = tvec - (w_sel ? startB : startA);
     }
+    *reinterpret_cast<uint4 *>(&s_lds[wave][lane >> 5][(lane & 31) * 16]) = svec;
     // (written and read by the same wave, LDS operations of a wave execute in order: no barrier needed)
     const uint8_t *m_byte = reinterpret_cast<const uint8_t *>(&m_lds[wave][my_sel * 8]) + (nl & 7);
-    const uint32_t *t_word = &t_lds[wave][(lane >> 5) * 8];
-    // the upper halves of FP8 blocks: 32 consecutive plane-H entries of each of the wave's two tiles
-    auto issue_h = [&](int c, SkinnyStage &st) {
-        st.h = ld64(hbuf, (uint32_t)lw.off_H + (t_word[c & 7] + spec_e) * 8u);
-    };
-#pragma unroll
-    for (int p = 0; p < kSkPrefetch; ++p) issue_h(p, ring[p]);
+    const uint16_t *s_pair = reinterpret_cast<const uint16_t *>(&s_lds[wave][my_sel][slot0]);
+    const uint32_t *t_rel = &t_lds[wave][my_sel * 8];
+    const uint2 *h_win = &h_lds[wave][my_sel][0];
 
-    // The activation loads were issued before the per-tile words that issue_h has just waited for, and
-    // loads complete in order: they have landed.
+    // The activation loads were issued before the per-tile words that the code above has waited for,
+    // and loads complete in order: they have landed.
     __syncthreads();
 
     float4_t acc[MT];
@@ -199,23 +245,19 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     const _Float16 *xrow = &xs[nl][32 * g];
     auto consume = [&](int c, const SkinnyStage &st) {
         const uint32_t mbits = (uint32_t)m_byte[c * 8] >> (2 * g);   // bits 0, 1: blocks 2g, 2g+1 are FP8
-        const uint32_t s0 = st.s & 0xFFu, s1 = (st.s >> 8) & 0xFFu;
+        const uint32_t sv = s_pair[c * (kTileSlots / 2)];
+        const uint32_t s0 = sv & 0xFFu, s1 = sv >> 8;
         const bool hi0 = mbits & 1u, hi1 = mbits & 2u;
-        // entry s of the lane's tile was fetched by lane 32 * my_sel + s
-        const int a0 = (my_sel * kSkSpec + (int)(s0 & (kSkSpec - 1))) << 2;
-        const int a1 = (my_sel * kSkSpec + (int)(s1 & (kSkSpec - 1))) << 2;
-        uint2 up0, up1;
-        up0.x = __builtin_amdgcn_ds_bpermute(a0, st.h.x);
-        up0.y = __builtin_amdgcn_ds_bpermute(a0, st.h.y);
-        up1.x = __builtin_amdgcn_ds_bpermute(a1, st.h.x);
-        up1.y = __builtin_amdgcn_ds_bpermute(a1, st.h.y);
-        // Tiles with more FP8 blocks than the speculative window: fetch directly.  Rare; the wait sits
+        // upper halves of FP8 blocks: entry (tile's offset in the window + index byte) of the staged window
+        const uint32_t trel = t_rel[c];
+        const uint32_t e0 = trel + s0, e1 = trel + s1;
+        uint2 up0 = h_win[e0 < (uint32_t)kSkHWin ? e0 : 0u], up1 = h_win[e1 < (uint32_t)kSkHWin ? e1 : 0u];
+        // K ranges with more FP8 blocks than the window holds: fetch directly.  Rare; the wait sits
         // inside the branch so that the common path keeps counting only its own prefetches.
         if (any_far) {
-            const bool far0 = hi0 && s0 >= (uint32_t)kSkSpec, far1 = hi1 && s1 >= (uint32_t)kSkSpec;
-            const uint32_t my_t = t_lds[wave][my_sel * 8 + c];
-            if (far0) up0 = ld64(hbuf, (uint32_t)lw.off_H + (my_t + s0) * 8u);
-            if (far1) up1 = ld64(hbuf, (uint32_t)lw.off_H + (my_t + s1) * 8u);
+            const uint32_t my_start = my_sel ? startB : startA;
+            if (hi0 && e0 >= (uint32_t)kSkHWin) up0 = ld64(hbuf, a.off_H + (my_start + e0) * 8u);
+            if (hi1 && e1 >= (uint32_t)kSkHWin) up1 = ld64(hbuf, a.off_H + (my_start + e1) * 8u);
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         }
         half2_t b[16];   // b[4 j + i]: halves 2i, 2i+1 of MFMA j's operand
@@ -241,8 +283,7 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
         for (int p = 0; p < kSkPrefetch; ++p) {
             const int c = c0r + p;
             if (c < ncols) consume(c, ring[p]);
-            issue_ls(c + kSkPrefetch, ring[p]);
-            issue_h(c + kSkPrefetch, ring[p]);
+            issue_l(c + kSkPrefetch, ring[p]);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the prefetches issued past the K range
@@ -252,7 +293,7 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     // acc[mt][r] = partial Y[m = 16 mt + 4 (lane / 16) + r][n = 64 rg + 16 wave + lane % 16]
     // operands whose headers do not match the call's shapes count as zeros
     const bool ok = w_ok && x_ok;
-    const float ss = xh.tensor_scale * wh.tensor_scale;
+    const float ss = x_scale * w_scale;
     const int64_t n = rg * kRows + wave * 16 + nl;
     if (ksplit == 1) {
 #pragma unroll
@@ -332,7 +373,7 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     // about three workgroups per CU, at most 8 K-tiles each
     const int64_t target_wgs = p.mt == 1 ? 768 : 384;
     int64_t want = (target_wgs + p.row_groups - 1) / p.row_groups;
-    int max_cols = kSkMaxCols;
+    const int max_cols = skinny_max_cols(p.mt);
     const int64_t need = (lw.n_kt + max_cols - 1) / max_cols;
     if (want < need) want = need;
     if (want > kSkMaxSplit) want = kSkMaxSplit;
@@ -379,9 +420,12 @@ fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const 
     if (!xh || !x16 || ld16 < lx.n_kt * kTileK || (uintptr_t)x16 % 16 != 0 || (ld16 * 2) % 16 != 0)
         return FGMP_ERR_BAD_SHAPE;
     SkinnyArgs a;
-    a.w = w; a.lw = lw;
-    a.xh = xh; a.lx = lx;
+    a.w = w; a.xh = xh;
     a.x16 = x16; a.ld16 = ld16;
+    a.w_rows = lw.rows; a.w_K = lw.K; a.x_rows = lx.rows; a.x_K = lx.K;
+    a.off_L = (uint32_t)lw.off_L; a.off_S = (uint32_t)lw.off_S; a.off_M = (uint32_t)lw.off_M;
+    a.off_T = (uint32_t)lw.off_T; a.off_H = (uint32_t)lw.off_H; a.n_tiles = (uint32_t)lw.n_tiles;
+    a.n_kt = (int)lw.n_kt;
     a.cols_per_wg = p.cols_per_wg; a.ksplit = p.ksplit;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.partial_bytes = (uint32_t)partial_bytes;
