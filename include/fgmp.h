@@ -54,7 +54,8 @@ typedef struct {
     int32_t compact;       /* 1: FP8 upper halves stored densely (weights) */
     int64_t n_blocks;      /* rows * K / 16 */
     int64_t n_fp8_blocks;  /* blocks kept in FP8 */
-    int64_t bytes_used;    /* bytes a reader touches / a compact tensor occupies */
+    int64_t bytes_used;    /* no reader touches a byte at or beyond this offset: a packed tensor may be
+                              copied into a 16-byte aligned buffer of this many bytes and used there */
 } fgmp_packed_info_t;
 
 /* Library version and the name of the target architecture ("gfx950"). */
@@ -80,7 +81,10 @@ size_t fgmp_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *              channel, shared by all rows; else N x K with that leading dim
  *   threshold  FP32; +INF keeps every block in FP4, -INF every block in FP8
  *   tensor_scale  S > 0: stored value = w / S; shared by both formats
- *   packed_W   out, packed_bytes >= fgmp_packed_bytes(N, K)
+ *   packed_W   out, packed_bytes >= fgmp_packed_bytes(N, K): the worst case is needed while packing;
+ *              afterwards fgmp_packed_info reports bytes_used, and the first bytes_used bytes are a
+ *              complete packed tensor wherever they are copied (this is where the memory saving
+ *              of Sec. 5.4.1 materializes)
  *   scores_out nullable, N*K/16 FP32 scores, row-major
  */
 fgmp_status_t fgmp_quantize_weights(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
@@ -112,7 +116,10 @@ fgmp_status_t fgmp_quantize_activations(const void *X, fgmp_dtype_t dt, int64_t 
  *   Y          out, M x N FP32, leading dimension ldy >= N
  *   workspace  >= fgmp_workspace_bytes(M, N, K) bytes of scratch (the decoded
  *              FP16 operands live here during the call)
- * Operands whose headers do not match (M, K) / (N, K) are treated as zeros.
+ * Operands whose headers do not match (M, K) / (N, K) are treated as zeros
+ * (the planes of fixed extent -- all but the FP8 upper halves -- are still read
+ * at the offsets (M, K) / (N, K) imply, so each buffer must hold a packed tensor
+ * of the stated shape or at least fgmp_packed_bytes bytes).
  */
 fgmp_status_t fgmp_gemm(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
                         float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);

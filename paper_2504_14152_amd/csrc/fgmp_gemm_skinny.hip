@@ -19,12 +19,15 @@
 // a compact tensor) -- are fetched in bulk at the start, with full-width loads,
 // and parked in LDS, where each lane picks its bytes per tile.
 //
-// The kernel is bound by vector-ALU issue, not by HBM, so address arithmetic is
-// kept off the vector unit: every access to the packed tensors is a buffer load
-// whose per-lane offset is computed once and whose per-K-tile displacement is an
-// immediate.  The buffer range check also makes every load safe without a
-// select: tiles past the K range or rows past the tensor read other tiles'
-// bytes or zeros, and their results are never stored.
+// A call lasts 10-30 us, so what matters is the chain of dependent steps a wave
+// goes through (per-wave time stamps: about a third each for start-up -- kernel
+// arguments, first loads, the plane-T -> plane-H dependency --, the K-tile loop,
+// and the split-K hand-over), not instruction count alone.  Every access to the
+// packed tensors is a buffer load whose per-lane offset is computed once and
+// whose per-K-tile displacement is a scalar offset.  The buffer range check
+// also makes every load safe without a select: tiles past the K range or rows
+// past the tensor read other tiles' bytes or zeros, and their results are
+// never stored.
 #include <cstddef>
 
 #include "fgmp_gemm_common.hpp"
@@ -40,7 +43,7 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 // CU with 4 waves and up to 16 rows of X, 2 per CU with 8 waves and 17..32 rows).
 constexpr int skinny_max_cols(int mt) { return mt == 1 ? 8 : 7; }
 constexpr int skinny_h_window(int mt) { return mt == 1 ? 192 : 64; }
-constexpr int kSkPrefetch = 4;    // plane-L/S K-tiles in flight per wave
+constexpr int kSkPrefetch = 4;    // plane-L K-tiles in flight per wave (2..4 measure alike, 8 is slower)
 constexpr int kSkXPad = 8;        // halves of padding per LDS activation row
 
 constexpr int kSkSumPass = 4;     // partial tiles summed per pass (their loads are in flight together)
@@ -107,10 +110,6 @@ struct SkinnyArgs {
     int n_kt, cols_per_wg, ksplit;
 };
 
-// The code is kept small on purpose (a rolled K-tile loop with a rotating register ring instead of a
-// fully unrolled body): every launch starts with a cold instruction cache, each wave runs the code
-// once, and straight-line code of several thousand instructions made instruction fetch, not HBM, the
-// limit of this kernel.
 // kWaves waves per workgroup, 16 weight rows each; they share the activations in LDS.
 template <int MT, int kWaves>
 __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)

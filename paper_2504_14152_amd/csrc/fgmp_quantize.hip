@@ -346,7 +346,8 @@ __global__ __launch_bounds__(1024) void scan_tiles_kernel(uint32_t *T, int64_t n
     }
     if (tid == 1023) {
         hdr->h_entries = part[1023];
-        hdr->bytes_used = off_H + part[1023] * 8;
+        // at least one entry stays readable: kernels that load plane H unconditionally read entry 0
+        hdr->bytes_used = off_H + (part[1023] > 0 ? part[1023] : 1) * 8;
     }
 }
 

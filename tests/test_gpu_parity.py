@@ -372,6 +372,31 @@ def test_gemm_decode_shapes(M, K, N, p):
     assert torch.equal(Y, Yf)
 
 
+@pytest.mark.parametrize("M,K,N,p", [(4, 1024, 200, 0.1), (24, 2048, 136, 0.3), (300, 512, 264, 0.1),
+                                     (8, 256, 72, 0.0), (300, 256, 72, 0.0)])
+def test_compact_weights_relocated_to_bytes_used(M, K, N, p):
+    """A compact weight tensor copied into a buffer of exactly bytes_used bytes
+    (poisoned guard bytes after it) gives the same product, bit for bit, and
+    unpacks to the same codes: no reader depends on bytes beyond bytes_used."""
+    _say(f"relocated compact weights M={M} K={K} N={N} p={p}")
+    c = _quantized_pair(M, K, N, 17, p, per_elem_w=False)
+    pW = c["pW"]
+    used = fgmp.packed_info(pW)["bytes_used"]
+    assert used <= pW.buf.numel()
+    n16 = -(-used // 16) * 16
+    small = torch.full((n16 + 4096,), 0xFF, dtype=torch.uint8, device=DEV)
+    small[:used] = pW.buf[:used]
+    pS = fgmp.Packed(small[:n16], N, K)
+    Y0 = fgmp.gemm(c["pX"], pW)
+    Y1 = fgmp.gemm(c["pX"], pS)
+    assert torch.equal(Y0, Y1)
+    Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], pS)
+    assert torch.equal(Y0, Yf)
+    for u, v in zip(fgmp.unpack_canonical(pW), fgmp.unpack_canonical(pS)):
+        assert torch.equal(u, v)
+    assert bool((small[n16:] == 0xFF).all())
+
+
 def test_gemm_two_pass_path_in_subprocess():
     """The alternative prefill path (both operands expanded to FP16 first) is chosen
     once per process by FGMP_PREFILL_KERNEL=dense; check it in a child process."""
