@@ -12,6 +12,8 @@
 // offset.  Loads run two K-steps ahead in registers (plane-H entries one step
 // ahead, since their address needs the mask and index bytes); every load is
 // unconditional, so outstanding loads can be counted at compile time.
+#include <type_traits>
+
 #include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
@@ -19,9 +21,12 @@ namespace fgmp {
 struct BRegs {
     uint4 l;       // plane L: two adjacent blocks
     uint32_t s;    // plane S: their two bytes
-    uint64_t m;    // plane M word of the tile
+    uint2 m;       // plane M word of the tile
     uint32_t t;    // plane T entry of the tile
 };
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 template <int kWM, int kWN>
 __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Float16 *__restrict__ A, int64_t ld,
@@ -41,81 +46,77 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     int64_t tm, tn;
     tile_coords(n_tm, n_tn, tm, tn);
 
-    // ---- A: direct global -> LDS, chunk swizzle applied on the global side ----
+    // ---- A: direct global -> LDS, chunk swizzle applied on the global side.  The address is a uniform
+    // base (tile row, K-step) plus a per-lane 32-bit offset that never changes, so the loop spends no
+    // vector instructions on it. ----
     const int lr = lane >> 3, lc = (lane & 7) ^ (((wave * 8 + lr) >> 1) & 7);
-    const char *ga = reinterpret_cast<const char *>(A + (tm * kBM + wave * 8 + lr) * ld) + lc * 16;
-    const int64_t row_step = kWaves * 8 * ld * 2;
+    const char *a_tile = reinterpret_cast<const char *>(A + tm * kBM * ld);
+    uint32_t a_off[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) a_off[i] = (uint32_t)((kWaves * 8 * i + wave * 8 + lr) * ld * 2 + lc * 16);
     auto issue_a = [&](int kt, int stage) {
+        const char *base = a_tile + (int64_t)kt * kRowBytes;
 #pragma unroll
         for (int i = 0; i < kLoads; ++i)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(ga + i * row_step + (int64_t)kt * kRowBytes),
+            __builtin_amdgcn_global_load_lds((global_void_t *)(base + a_off[i]),
                                              (lds_void_t *)&lds[stage][0][(kWaves * i + wave) * 1024], 16, 0, 0);
     };
 
-    // ---- B: packed weights through registers ----
+    // ---- B: packed weights through registers.  Buffer loads: the per-thread offset is computed once,
+    // the K-step displacement is uniform and travels in the scalar offset (no vector address math in
+    // the loop).  Tile indices are clamped into the tensor, so every index read from it is valid. ----
+    const __amdgpu_buffer_rsrc_t wbuf =
+        __builtin_amdgcn_make_buffer_rsrc(W.hdr, 0, (int)(uint32_t)lw.total_bytes, 0x00020000);
     const int br = tid >> 1, bp = tid & 1;
     const int64_t row_b = tn * kBN + br;
-    const bool b_ok = (row_b >> 3) < lw.n_rt;
-    const int64_t rt_b = b_ok ? (row_b >> 3) : lw.n_rt - 1;   // rows beyond the tensor read a valid tile, are zeroed
+    // rows beyond the tensor read a valid tile; their products only reach output columns that are never stored
+    const uint32_t rt_b = (uint32_t)((row_b >> 3) < lw.n_rt ? (row_b >> 3) : lw.n_rt - 1);
     const int r8 = (int)(row_b & 7);
     const int swz_b = (br >> 1) & 7;
     const int last_kt = nk - 1;
-    auto slot_of = [&](int kt) { return r8 * kTileBlocks + (kt & 1) * 4 + 2 * bp; };
+    const uint32_t tile_b = rt_b * (uint32_t)lw.n_kt;                       // first tile of the thread's row-tile
+    const uint32_t vL = (uint32_t)lw.off_L + (tile_b * kTileSlots + r8 * kTileBlocks + 2 * bp) * 8u;
+    const uint32_t vS = (uint32_t)lw.off_S + tile_b * kTileSlots + r8 * kTileBlocks + 2 * bp;
+    const uint32_t vM = (uint32_t)lw.off_M + tile_b * 8u;
+    const uint32_t vT = (uint32_t)lw.off_T + tile_b * 4u;
+    const uint32_t off_H = (uint32_t)lw.off_H;
+    const int m_shift = (r8 & 3) * 8 + 2 * bp;   // bit of the thread's first block of an even K-step in its mask dword
     auto load_b = [&](int kt, BRegs &b) {
         kt = kt < last_kt ? kt : last_kt;
-        const int64_t tile = rt_b * lw.n_kt + (kt >> 1);
-        const int64_t slot = tile * kTileSlots + slot_of(kt);
-        b.l = *reinterpret_cast<const uint4 *>(&W.L[slot]);
-        b.s = *reinterpret_cast<const uint16_t *>(&W.S[slot]);
-        b.m = W.M[tile];
-        b.t = W.T[tile];
+        const uint32_t t2 = (uint32_t)__builtin_amdgcn_readfirstlane(kt) >> 1, odd = (uint32_t)__builtin_amdgcn_readfirstlane(kt) & 1u;   // K-tile, and which half of its 8 blocks
+        const u32x4_t l = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)vL, (int)(t2 * (kTileSlots * 8) + odd * 32), 0);
+        b.l = make_uint4(l[0], l[1], l[2], l[3]);
+        b.s = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(wbuf, (int)vS, (int)(t2 * kTileSlots + odd * 4), 0);
+        const u32x2_t m = __builtin_amdgcn_raw_buffer_load_b64(wbuf, (int)vM, (int)(t2 * 8), 0);
+        b.m = make_uint2(m[0], m[1]);
+        b.t = __builtin_amdgcn_raw_buffer_load_b32(wbuf, (int)vT, (int)(t2 * 4), 0);
+    };
+    // bits 0, 1 of the result: the thread's two blocks of K-step kt are FP8
+    auto hi_bits = [&](int kt, const BRegs &b) {
+        kt = kt < last_kt ? kt : last_kt;
+        const uint32_t word = r8 < 4 ? b.m.x : b.m.y;
+        return (word >> (m_shift + (kt & 1) * 4)) & 3u;
     };
     auto load_h = [&](int kt, const BRegs &b, uint2 (&h)[2]) {
-        kt = kt < last_kt ? kt : last_kt;
-        const int s0 = slot_of(kt);
+        const uint32_t bits = hi_bits(kt, b);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const bool hi = (b.m >> (s0 + j)) & 1ull;
-            const uint64_t idx = hi ? (uint64_t)b.t + ((b.s >> (8 * j)) & 0xFFu) : 0ull;
-            h[j] = W.H[idx];
+            const bool hi = (bits >> j) & 1u;
+            const uint32_t idx = hi ? b.t + ((b.s >> (8 * j)) & 0xFFu) : 0u;
+            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(wbuf, (int)(off_H + idx * 8u), 0, 0);
+            h[j] = make_uint2(v[0], v[1]);
         }
     };
     auto decode_store = [&](int kt, const BRegs &b, const uint2 (&h)[2], int stage, int j) {
-        kt = kt < last_kt ? kt : last_kt;
-        const int s0 = slot_of(kt);
+        const uint32_t bits = hi_bits(kt, b);
         char *row = &lds[stage][1][br * kRowBytes];
-        {
-            const bool hi = (b.m >> (s0 + j)) & 1ull;
-            const uint32_t w0 = j ? b.l.z : b.l.x, w1 = j ? b.l.w : b.l.y;
-            half2_t v[8];
-            if (hi) {
-                v[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, false);
-                v[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, true);
-                v[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, false);
-                v[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, true);
-                v[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(h[j].x, 1.0f, false);
-                v[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(h[j].x, 1.0f, true);
-                v[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(h[j].y, 1.0f, false);
-                v[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(h[j].y, 1.0f, true);
-            } else {
-                const uint32_t sb = (b.s >> (8 * j)) & 0xFFu;
-                const half2_t sc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sb | (sb << 8), 1.0f, false);
-                v[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w0, 1.0f, 0) * sc;
-                v[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w0, 1.0f, 1) * sc;
-                v[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w0, 1.0f, 2) * sc;
-                v[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w0, 1.0f, 3) * sc;
-                v[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w1, 1.0f, 0) * sc;
-                v[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w1, 1.0f, 1) * sc;
-                v[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w1, 1.0f, 2) * sc;
-                v[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w1, 1.0f, 3) * sc;
-            }
-            uint32_t o[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) o[i] = b_ok ? __builtin_bit_cast(uint32_t, v[i]) : 0u;
-            const int c = 2 * (2 * bp + j);   // the block's two 16-byte chunks within the 128-byte row
-            *reinterpret_cast<uint4 *>(row + ((c ^ swz_b) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
-            *reinterpret_cast<uint4 *>(row + (((c + 1) ^ swz_b) << 4)) = make_uint4(o[4], o[5], o[6], o[7]);
-        }
+        half2_t v[8];
+        decode_block(j ? make_uint2(b.l.z, b.l.w) : make_uint2(b.l.x, b.l.y), (b.s >> (8 * j)) & 0xFFu,
+                     (bits >> j) & 1u, h[j], v);
+        const uint32_t *o = reinterpret_cast<const uint32_t *>(v);
+        const int c = 2 * (2 * bp + j);   // the block's two 16-byte chunks within the 128-byte row
+        *reinterpret_cast<uint4 *>(row + ((c ^ swz_b) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<uint4 *>(row + (((c + 1) ^ swz_b) << 4)) = make_uint4(o[4], o[5], o[6], o[7]);
     };
 
     float16_t acc[TM][TN];
@@ -167,8 +168,10 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     // Iteration kt multiplies K-step kt (stage kt & 1) and, before its barrier,
     // decodes K-step kt + 1 into the other stage; after the barrier that stage is
     // readable and the stage just consumed takes the A loads of K-step kt + 2.
-    for (int kt = 0; kt < nk; ++kt) {
-        const int st = kt & 1;
+    // (the body is instantiated for both LDS stages, so every LDS address in it is a register plus an
+    // immediate; nk is even because the K extent is padded to whole 128-element tiles)
+    auto k_step = [&](int kt, auto stage_c) {
+        constexpr int st = decltype(stage_c)::value;
         load_b(kt + 3, far);            // 4 register loads ...
         load_h(kt + 2, nxt, hnxt);      // ... + 2: the only loads younger than the A loads at this iteration's barrier
         read_frags(st, 1, fa[1], fb[1]);
@@ -211,6 +214,10 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         hcur[0] = hnxt[0];
         hcur[1] = hnxt[1];
         nxt = far;
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+        k_step(kt, std::integral_constant<int, 0>{});
+        k_step(kt + 1, std::integral_constant<int, 1>{});
     }
     __builtin_amdgcn_s_waitcnt(0);
 
