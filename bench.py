@@ -2,9 +2,12 @@
 """Benchmark of the FGMP hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic input:
-on-the-fly activation quantization (scoring, FP8/NVFP4 decision, packing)
+on-the-fly activation quantization (scoring, FP8/NVFP4 decision, encoding)
 followed by the block-mixed-precision GEMM against pre-quantized weights,
-issued as one fgmp_quant_gemm_fused call.  The workload is the Llama-2-7B
+issued as one fgmp_quant_gemm_fused call (which hands the quantized
+activations to the GEMM as the FP16 values of their codes instead of writing
+the packed form; `extra.unfused_ms_per_step` times the same work as
+fgmp_quantize_activations + fgmp_gemm through the packed form).  The workload is the Llama-2-7B
 fused QKV projection at 4K context: X 4096 x 4096 bf16 with 1% outlier
 channels, W 12288 x 4096 pre-quantized with 10% FP8 blocks, 10% FP8
 activation blocks.  Inputs are resident in HBM before the timed region.
@@ -157,6 +160,11 @@ def main() -> int:
     # the same product from packed activations (fgmp_gemm: expands X to FP16 first), and the packing quantizer
     ms_gemm = timed(lambda: fgmp.gemm(pX, pW, out=Y, workspace=ws), args.steps, 20)
     ms_quant = timed(lambda: fgmp.quantize_activations(xd, fxd, Tx, sx, out=pX), args.steps, 20)
+
+    def unfused():
+        fgmp.quantize_activations(xd, fxd, Tx, sx, out=pX)
+        fgmp.gemm(pX, pW, out=Y, workspace=ws)
+    ms_unfused = timed(unfused, args.steps, 20)
     roofline = {"bound": "mfma", "kernel": "gemm_mixed_kernel", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
                 "traffic": GEMM_KERNEL_HBM_BYTES, "ms_per_launch": round(ms_kernel, 4),
@@ -176,7 +184,8 @@ def main() -> int:
         "roofline": roofline,
     }
 
-    extra = {"ms_quantize_x": round(ms_quant, 4), "ms_gemm": round(ms_gemm, 4), "host_ms_per_step": round(t_host, 4)}
+    extra = {"ms_quantize_x": round(ms_quant, 4), "ms_gemm": round(ms_gemm, 4), "host_ms_per_step": round(t_host, 4),
+             "unfused_ms_per_step": round(ms_unfused, 4)}
     x_bytes = M * K * 2 + (M * K // 16) * bytes_per_block(P_FP8)
     extra["act_quant_prefill_GBps"] = round(x_bytes / (ms_quant * 1e-3) / 1e9, 1)
 
