@@ -154,9 +154,15 @@ void fgmp_oracle_e4m3_encode_many(const float *r, int64_t n, uint8_t *out)
  * S is the tensor's FP32 scale, T the calibrated threshold.
  * Writes 16 code bytes (E2M1 nibble value 0..15, or E4M3 byte), the E4M3
  * block scale (0 for an FP8 block), the mask (1 = FP8) and the score. */
+/* score_mode 0: the block's score is the sensitivity-weighted NVFP4 error
+ * [Eq. 6 with the low-precision error of Eq. 2].  score_mode 1: the weighted
+ * square of the error *increase* from keeping the block in NVFP4 rather than
+ * FP8, Q_NVFP4(v) - Q_FP8(v) [Eq. 7, Eq. 8]; with the weights set to one, or
+ * to the other operand's mean squared channel magnitude, the same sum is the
+ * "quantization error" and "output error" baseline policy [Sec. 3.4, Eq. 12, Eq. 13]. */
 static void quantize_block(const float *x, const float *f, float S, float T,
-                           uint8_t *codes, uint8_t *scale, uint8_t *mask,
-                           float *score)
+                           int score_mode, uint8_t *codes, uint8_t *scale,
+                           uint8_t *mask, float *score)
 {
     const float inv_S = 1.0f / S;
     const float S6 = 6.0f * S; /* largest E2M1 magnitude times the tensor scale */
@@ -188,7 +194,14 @@ static void quantize_block(const float *x, const float *f, float S, float T,
         }
         /* quantization error [Eq. 2] and its sensitivity-weighted square
          * [Eq. 6]; the sign convention of the error does not matter */
-        float e = x[i] - xhat;
+        float e;
+        if (score_mode == 0) {
+            e = x[i] - xhat;
+        } else {
+            /* the same element kept in FP8: (Q4 - v) - (Q8 - v) = Q4 - Q8 */
+            float x8 = fgmp_oracle_e4m3_decode(fgmp_oracle_e4m3_encode(x[i] * inv_S)) * S;
+            e = xhat - x8;
+        }
         float e2 = e * e;
         t[i] = e2 * f[i];
     }
@@ -224,12 +237,13 @@ static void quantize_block(const float *x, const float *f, float S, float T,
  * Outputs (row-major, caller-allocated): codes rows*K bytes, scales / mask /
  * scores rows*K/16 entries.  Returns 0, or -1 on a bad argument (null pointer,
  * non-positive size, K not a multiple of 16, non-finite input or scale). */
-int fgmp_oracle_quantize(const float *x, int64_t rows, int64_t K, int64_t ldx,
-                         const float *fisher, int64_t ld_fisher, float T,
-                         float S, uint8_t *codes, uint8_t *scales,
-                         uint8_t *mask, float *scores)
+int fgmp_oracle_quantize_mode(const float *x, int64_t rows, int64_t K, int64_t ldx,
+                              const float *fisher, int64_t ld_fisher, float T,
+                              float S, int score_mode, uint8_t *codes,
+                              uint8_t *scales, uint8_t *mask, float *scores)
 {
     if (!x || !fisher || !codes || !scales || !mask || !scores) return -1;
+    if (score_mode != 0 && score_mode != 1) return -1;
     if (rows <= 0 || K <= 0 || K % FGMP_ORACLE_BLOCK != 0 || ldx < K) return -1;
     if (!(S > 0.0f) || !isfinite(S) || isnan(T)) return -1;
     const int64_t nb = K / FGMP_ORACLE_BLOCK;
@@ -242,12 +256,23 @@ int fgmp_oracle_quantize(const float *x, int64_t rows, int64_t K, int64_t ldx,
                               b * FGMP_ORACLE_BLOCK;
             for (int i = 0; i < FGMP_ORACLE_BLOCK; ++i)
                 if (!isfinite(xb[i]) || !isfinite(fb[i])) bad = 1;
-            quantize_block(xb, fb, S, T, codes + r * K + b * FGMP_ORACLE_BLOCK,
+            quantize_block(xb, fb, S, T, score_mode,
+                           codes + r * K + b * FGMP_ORACLE_BLOCK,
                            scales + r * nb + b, mask + r * nb + b,
                            scores + r * nb + b);
         }
     }
     return bad ? -1 : 0;
+}
+
+/* The default scoring [Eq. 6]. */
+int fgmp_oracle_quantize(const float *x, int64_t rows, int64_t K, int64_t ldx,
+                         const float *fisher, int64_t ld_fisher, float T,
+                         float S, uint8_t *codes, uint8_t *scales,
+                         uint8_t *mask, float *scores)
+{
+    return fgmp_oracle_quantize_mode(x, rows, K, ldx, fisher, ld_fisher, T, S, 0,
+                                     codes, scales, mask, scores);
 }
 
 /* Real value (without the tensor scale) of every stored element:

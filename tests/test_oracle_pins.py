@@ -165,6 +165,82 @@ def test_score_agrees_with_fp64_definition(per_element):
     assert np.all(np.abs(x.astype(np.float64) - xhat).reshape(x.shape[0], -1, 16).max(axis=2) <= 1.0 * d + 1e-12 + 1e-6 * np.abs(x).reshape(x.shape[0], -1, 16).max(axis=2) + (d == 0) * 1e9)
 
 
+# ---------------------------------------------------------------- Eq. 8 score ("delta" mode)
+
+def _both_reconstructions(x, f, S):
+    """x_hat in NVFP4 and in FP8 for every element, from two runs whose thresholds force each format."""
+    lo = orc.quantize(x, f, np.inf, S)           # every block NVFP4
+    hi = orc.quantize(x, f, -np.inf, S)          # every block FP8
+    assert not lo["mask"].any() and hi["mask"].all()
+    # the reconstructions are fp32 values: x4 = fp32(e2m1 * fp32(e4m3 * S)), x8 = fp32(e4m3 * S)
+    S64 = np.float64(np.float32(S))
+    e4 = _torch_e4m3_decode_all().astype(np.float64)
+    d32 = (e4[lo["scales"]] * S64).astype(np.float32).astype(np.float64)
+    e2 = np.array(E2M1 + [-v for v in E2M1])[lo["codes"]]
+    x4 = (e2 * np.repeat(d32, 16, axis=1)).astype(np.float32).astype(np.float64)
+    x8 = (orc.dequantize(hi["codes"], hi["scales"], hi["mask"]) * S64).astype(np.float32).astype(np.float64)
+    np.testing.assert_allclose(x4, orc.dequantize(lo["codes"], lo["scales"], lo["mask"]) * S64, rtol=2e-7)
+    return x4, x8
+
+
+@pytest.mark.parametrize("per_element", [False, True])
+def test_delta_score_agrees_with_fp64_definition(per_element):
+    """Eq. 8: sum F (Q_FP4(v) - Q_FP8(v))^2, recomputed in fp64 from the two
+    encodings produced by separate all-FP4 and all-FP8 runs."""
+    x, f, S = _random_case(per_element=per_element)
+    q4, q8 = _both_reconstructions(x, f, S)
+    w = f.astype(np.float64) if per_element else f.astype(np.float64)[None, :]
+    want = ((q4 - q8) ** 2 * w).reshape(x.shape[0], -1, 16).sum(axis=2)
+    got = orc.quantize(x, f, np.inf, S, score_mode="delta")["scores"]
+    assert np.all(got >= 0)
+    np.testing.assert_allclose(got, want, rtol=2e-6, atol=0)
+    # the two scores differ (otherwise the mode switch does nothing) but are related through the
+    # triangle inequality on the block's weighted error vectors: sqrt(I') <= sqrt(I_fp4) + sqrt(I_fp8)
+    base = orc.quantize(x, f, np.inf, S)["scores"].astype(np.float64)
+    assert not np.array_equal(got, base.astype(np.float32))
+    i8 = ((x.astype(np.float64) - q8) ** 2 * w).reshape(x.shape[0], -1, 16).sum(axis=2)
+    assert np.all(np.sqrt(want) <= (np.sqrt(base) + np.sqrt(i8)) * (1 + 1e-5) + 1e-30)
+
+
+def test_delta_score_is_zero_when_both_formats_agree():
+    """Values that NVFP4 and FP8 both represent exactly give Q_FP4 = Q_FP8, so
+    Eq. 8 is zero while nothing else about the encoding changes."""
+    rng = np.random.default_rng(5)
+    mags = np.array(E2M1, dtype=np.float32)
+    S = 0.5
+    x = (rng.choice(mags, size=(8, 64)) * rng.choice([-1.0, 1.0], size=(8, 64))).astype(np.float32)
+    x[:, ::16] = 6.0              # every block's maximum is 6: block scale 1/S
+    x *= np.float32(S) * 2.0      # e2m1 * (E4M3 scale 2) * S, all exactly FP8-representable after / S
+    f = synth.fisher_per_channel(64, 5, 1)
+    d = orc.quantize(x, f, 0.0, S, score_mode="delta")
+    e = orc.quantize(x, f, 0.0, S)
+    assert not d["scores"].any() and not e["scores"].any() and not d["mask"].any()
+    for k in ("codes", "scales", "mask"):
+        assert np.array_equal(d[k], e[k])
+
+
+def test_delta_mode_changes_only_scores_and_decisions():
+    """At a fixed decision the stored codes do not depend on the score mode;
+    with unit weights the score is the plain squared difference (the
+    quantization-error policy, Eq. 12); scaling the weights scales it (Eq. 13)."""
+    x, f, S = _random_case()
+    for T in (np.inf, -np.inf):
+        a, b = orc.quantize(x, f, T, S), orc.quantize(x, f, T, S, score_mode="delta")
+        for k in ("codes", "scales", "mask"):
+            assert np.array_equal(a[k], b[k])
+    q4, q8 = _both_reconstructions(x, f, S)
+    ones = np.ones(x.shape[1], dtype=np.float32)
+    qe = orc.quantize(x, ones, np.inf, S, score_mode="delta")["scores"]
+    np.testing.assert_allclose(qe, ((q4 - q8) ** 2).reshape(x.shape[0], -1, 16).sum(axis=2), rtol=2e-6)
+    oe = orc.quantize(x, 4.0 * ones, np.inf, S, score_mode="delta")["scores"]
+    assert np.array_equal(oe, 4.0 * qe)
+    # power-of-two rescaling of the tensor leaves the decisions unchanged
+    T = orc.threshold(orc.quantize(x, f, np.inf, S, score_mode="delta")["scores"], 0.2)
+    m0 = orc.quantize(x, f, T, S, score_mode="delta")["mask"]
+    m1 = orc.quantize(4.0 * x, f, 16.0 * T, 4.0 * S, score_mode="delta")["mask"]
+    assert np.array_equal(m0, m1) and abs(m0.mean() - 0.2) < 0.01
+
+
 def test_block_scale_is_dynamic_max():
     """The stored block scale is the E4M3 code nearest to amax / (6 S)."""
     x, f, S = _random_case()
