@@ -47,6 +47,15 @@ enum {
 
 typedef enum { FGMP_F32 = 0, FGMP_BF16 = 1 } fgmp_dtype_t;
 
+/* What a block's score measures (the *_ex entry points; the plain ones use FGMP_SCORE_NVFP4_ERROR).
+ *   FGMP_SCORE_NVFP4_ERROR  sum_i F_i (x_i - Q_NVFP4(x_i))^2              (Eq. 6)
+ *   FGMP_SCORE_DELTA        sum_i F_i (Q_NVFP4(x_i) - Q_FP8(x_i))^2       (Eq. 7, Eq. 8): the error increase
+ *                           from keeping the block in NVFP4 rather than FP8.  With F = 1 this is the
+ *                           "quantization error" policy (Eq. 12), with F = the other operand's mean
+ *                           squared channel magnitude the "output error" policy (Eq. 13; Sec. 3.4).
+ * The stored codes of a block depend only on the decision, not on the mode. */
+typedef enum { FGMP_SCORE_NVFP4_ERROR = 0, FGMP_SCORE_DELTA = 1 } fgmp_score_mode_t;
+
 /* Host-side summary of a packed tensor (fgmp_packed_info). */
 typedef struct {
     int64_t rows, K;
@@ -133,6 +142,23 @@ fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, i
                                     const float *fisher_k, float threshold, float scale_x,
                                     const void *packed_W, int64_t N, float *Y, int64_t ldy,
                                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The three calls above with the score selected by `score_mode` (Sec. 3.1, Eq. 8; Sec. 3.4);
+ * all other arguments, outputs and errors as the plain calls.  FGMP_ERR_INVALID_ARG for an unknown mode.
+ */
+fgmp_status_t fgmp_quantize_weights_ex(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
+                                       const float *fisher, int64_t ld_fisher, float threshold,
+                                       float tensor_scale, fgmp_score_mode_t score_mode, void *packed_W,
+                                       size_t packed_bytes, float *scores_out, void *stream);
+fgmp_status_t fgmp_quantize_activations_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                           const float *fisher_k, float threshold, float tensor_scale,
+                                           fgmp_score_mode_t score_mode, void *packed_X, size_t packed_bytes,
+                                           float *scores_out, void *stream);
+fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                       const float *fisher_k, float threshold, float scale_x,
+                                       fgmp_score_mode_t score_mode, const void *packed_W, int64_t N, float *Y,
+                                       int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Expand a packed tensor to layout-independent arrays (for tests and tools):

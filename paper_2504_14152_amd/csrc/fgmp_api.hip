@@ -57,6 +57,35 @@ fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, i
                       workspace_bytes, as_stream(stream));
 }
 
+fgmp_status_t fgmp_quantize_weights_ex(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
+                                       const float *fisher, int64_t ld_fisher, float threshold,
+                                       float tensor_scale, fgmp_score_mode_t score_mode, void *packed_W,
+                                       size_t packed_bytes, float *scores_out, void *stream)
+{
+    return quantize_tensor(W, dt, N, K, ldw, fisher, ld_fisher, threshold, tensor_scale, packed_W,
+                           packed_bytes, scores_out, /*compact=*/true, as_stream(stream), nullptr, 0, nullptr, 0,
+                           (int)score_mode);
+}
+
+fgmp_status_t fgmp_quantize_activations_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                           const float *fisher_k, float threshold, float tensor_scale,
+                                           fgmp_score_mode_t score_mode, void *packed_X, size_t packed_bytes,
+                                           float *scores_out, void *stream)
+{
+    return quantize_tensor(X, dt, M, K, ldx, fisher_k, /*ld_fisher=*/0, threshold, tensor_scale, packed_X,
+                           packed_bytes, scores_out, /*compact=*/false, as_stream(stream), nullptr, 0, nullptr, 0,
+                           (int)score_mode);
+}
+
+fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                       const float *fisher_k, float threshold, float scale_x,
+                                       fgmp_score_mode_t score_mode, const void *packed_W, int64_t N, float *Y,
+                                       int64_t ldy, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Y, ldy, workspace,
+                      workspace_bytes, as_stream(stream), (int)score_mode);
+}
+
 fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K, uint8_t *codes,
                                     uint8_t *scales, uint8_t *mask, void *stream)
 {

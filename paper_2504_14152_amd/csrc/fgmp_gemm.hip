@@ -309,7 +309,7 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
 // and the two-pass path go through the packed activations.
 fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
                          float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
-                         void *workspace, size_t workspace_bytes, hipStream_t st)
+                         void *workspace, size_t workspace_bytes, hipStream_t st, int score_mode)
 {
     if (!workspace || !packed_W || !Y) return FGMP_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
@@ -325,7 +325,8 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
         char *sws = ws + kHeaderBytes + skinny_x16_bytes(M, K);
         const SkinnyCounters ctr = gemm_skinny_counters(M, N, K, sws);
         const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws,
-                                                 sizeof(PackedHeader), nullptr, false, st, x16, ld16, ctr.ptr, ctr.n);
+                                                 sizeof(PackedHeader), nullptr, false, st, x16, ld16, ctr.ptr, ctr.n,
+                                                 score_mode);
         if (rc != FGMP_OK) return rc;
         return gemm_skinny(reinterpret_cast<const PackedHeader *>(ws), make_layout(M, K), x16, ld16, packed_W,
                            make_layout(N, K), M, N, K, Y, ldy, sws, st);
@@ -337,7 +338,8 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
         PackedHeader *hx = reinterpret_cast<PackedHeader *>(ws);
         _Float16 *x16 = reinterpret_cast<_Float16 *>(ws + kHeaderBytes);
         const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws,
-                                                 sizeof(PackedHeader), nullptr, false, st, x16, w.ld);
+                                                 sizeof(PackedHeader), nullptr, false, st, x16, w.ld, nullptr, 0,
+                                                 score_mode);
         if (rc != FGMP_OK) return rc;
         const PackedLayout lb = make_layout(N, K);
         const PackedView B = make_view(const_cast<void *>(packed_W), lb);
@@ -346,7 +348,7 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
     }
     const size_t xbytes = (size_t)make_layout(M, K).total_bytes;
     const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws, xbytes,
-                                             nullptr, false, st);
+                                             nullptr, false, st, nullptr, 0, nullptr, 0, score_mode);
     if (rc != FGMP_OK) return rc;
     return gemm_packed(ws, M, packed_W, N, K, Y, ldy, ws + xbytes, workspace_bytes - xbytes, st);
 }

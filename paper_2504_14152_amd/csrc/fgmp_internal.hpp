@@ -22,7 +22,7 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
                               _Float16 *x16 = nullptr, int64_t ld16 = 0, uint32_t *zero = nullptr,
-                              int64_t zero_n = 0);
+                              int64_t zero_n = 0, int score_mode = FGMP_SCORE_NVFP4_ERROR);
 fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
                             uint8_t *mask, hipStream_t st);
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
@@ -31,7 +31,8 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 // quantize X and multiply in one call; `workspace` holds at least gemm_workspace_bytes(M, N, K)
 fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
                          float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
-                         void *workspace, size_t workspace_bytes, hipStream_t st);
+                         void *workspace, size_t workspace_bytes, hipStream_t st,
+                         int score_mode = FGMP_SCORE_NVFP4_ERROR);
 // Decode shapes (few rows of X): weight-streaming kernel.  X is given as FP16 values (`x16`,
 // gemm_skinny_x16_rows(M) rows of ld16 halves; rows from M rounded up to 8 on are never used for a
 // stored output) plus the header of its packed form.

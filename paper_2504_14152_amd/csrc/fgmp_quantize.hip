@@ -46,6 +46,7 @@ struct QuantParams {
     int64_t ld16;
     uint32_t *zero;        // words cleared by the first workgroup (counters of the kernel that follows)
     int zero_n;
+    bool delta;            // Eq. 8 scoring (see quantize_kernel)
 };
 
 // kModeF16 writes, instead of the packed planes, the FP16 value of every stored
@@ -134,7 +135,9 @@ template <bool kHW, bool kClamp> __device__ __forceinline__ void encode_fp8_bloc
 // workgroup work on 4 adjacent row-tiles of the same K-tile at a time, so the
 // per-channel sensitivities stay in registers across the loop.  The input of
 // the next row-tile is fetched while the current one is processed.
-template <typename Tin, bool kPerElem, bool kHW, int kMode>
+// kDelta: the score is Eq. 8's (weighted square of Q_NVFP4(x) - Q_FP8(x)) instead of Eq. 6's NVFP4 error;
+// the FP8 codes are then computed for every block and reused when the block is kept in FP8.
+template <typename Tin, bool kPerElem, bool kHW, int kMode, bool kDelta>
 __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -200,6 +203,18 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
         const float d = e4m3_decode_int(sc) * p.S;
         const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
 
+        // Eq. 8 scoring: the block's FP8 codes, needed for every block
+        uint32_t c8[4] = {0u, 0u, 0u, 0u};
+        if constexpr (kDelta) {
+            // values beyond the FP8 range only occur when the caller's S is below amax / 448
+            const bool any_big = __ballot(amax * inv_S > 448.0f) != 0ull;
+            float r[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+            if (any_big) encode_fp8_block<kHW, true>(r, c8);
+            else encode_fp8_block<kHW, false>(r, c8);
+        }
+
         // NVFP4 codes, reconstruction, weighted squared error
         uint32_t q[2] = {0u, 0u};
         float t[16];
@@ -212,7 +227,15 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
 #define FGMP_ERR(W, B, I)                                                                          \
     {                                                                                              \
         const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);                \
-        const float e0 = x[I] - v[0] * d, e1 = x[I + 1] - v[1] * d;                                \
+        float e0, e1;                                                                              \
+        if constexpr (kDelta) {                                                                    \
+            const float2_t v8 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c8[(I) / 4], 1.0f, ((I) % 4) >= 2); \
+            e0 = v[0] * d - v8[0] * p.S;                                                           \
+            e1 = v[1] * d - v8[1] * p.S;                                                           \
+        } else {                                                                                   \
+            e0 = x[I] - v[0] * d;                                                                  \
+            e1 = x[I + 1] - v[1] * d;                                                              \
+        }                                                                                          \
         t[I] = (e0 * e0) * f[I];                                                                   \
         t[I + 1] = (e1 * e1) * f[I + 1];                                                           \
     }
@@ -224,7 +247,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
             for (int i = 0; i < 16; ++i) {
                 const uint32_t c = e2m1_encode_int(x[i] * inv_d);
                 q[i >> 3] |= c << (4 * (i & 7));
-                const float e = x[i] - e2m1_decode_int(c) * d;
+                float e;
+                if constexpr (kDelta) e = e2m1_decode_int(c) * d - e4m3_decode_int((c8[i >> 2] >> (8 * (i & 3))) & 0xFFu) * p.S;
+                else e = x[i] - e2m1_decode_int(c) * d;
                 t[i] = (e * e) * f[i];
             }
         }
@@ -245,12 +270,17 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
             static_assert(kHW, "the FP16 output mode uses the conversion instructions");
             half2_t o[8];
             if (hi) {
-                float r[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
                 uint32_t c[4];
-                if (amax * inv_S > 448.0f) encode_fp8_block<kHW, true>(r, c);
-                else encode_fp8_block<kHW, false>(r, c);
+                if constexpr (kDelta) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) c[j] = c8[j];
+                } else {
+                    float r[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                    if (amax * inv_S > 448.0f) encode_fp8_block<kHW, true>(r, c);
+                    else encode_fp8_block<kHW, false>(r, c);
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     o[2 * j] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(c[j], 1.0f, false);
@@ -292,12 +322,17 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
                 // values beyond the FP8 range only occur when the caller's S is below amax / 448
                 const bool any_big = __ballot(hi && amax * inv_S > 448.0f) != 0ull;
                 if (hi) {
-                    float r[16];
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
                     uint32_t c[4];
-                    if (any_big) encode_fp8_block<kHW, true>(r, c);
-                    else encode_fp8_block<kHW, false>(r, c);
+                    if constexpr (kDelta) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) c[j] = c8[j];
+                    } else {
+                        float r[16];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                        if (any_big) encode_fp8_block<kHW, true>(r, c);
+                        else encode_fp8_block<kHW, false>(r, c);
+                    }
                     lword = make_uint2(c[0], c[1]);
                     p.out.H[(uint64_t)hbase + prefix] = make_uint2(c[2], c[3]);
                     sbyte = prefix;
@@ -399,10 +434,17 @@ static int pick_rt_per_wave(int64_t n_rt)
 template <typename Tin, int kMode>
 static void launch_quantize_mode(const QuantParams &p, bool per_elem, dim3 grid, hipStream_t st)
 {
-    if (per_elem)
-        hipLaunchKernelGGL((quantize_kernel<Tin, true, kUseHwCvt, kMode>), grid, dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL((quantize_kernel<Tin, false, kUseHwCvt, kMode>), grid, dim3(256), 0, st, p);
+    if (p.delta) {
+        if (per_elem)
+            hipLaunchKernelGGL((quantize_kernel<Tin, true, kUseHwCvt, kMode, true>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((quantize_kernel<Tin, false, kUseHwCvt, kMode, true>), grid, dim3(256), 0, st, p);
+    } else {
+        if (per_elem)
+            hipLaunchKernelGGL((quantize_kernel<Tin, true, kUseHwCvt, kMode, false>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((quantize_kernel<Tin, false, kUseHwCvt, kMode, false>), grid, dim3(256), 0, st, p);
+    }
 }
 
 template <typename Tin>
@@ -419,8 +461,9 @@ static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipS
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
-                              _Float16 *x16, int64_t ld16, uint32_t *zero, int64_t zero_n)
+                              _Float16 *x16, int64_t ld16, uint32_t *zero, int64_t zero_n, int score_mode)
 {
+    if (score_mode != FGMP_SCORE_NVFP4_ERROR && score_mode != FGMP_SCORE_DELTA) return FGMP_ERR_INVALID_ARG;
     if (!X || !fisher || (!packed && !x16)) return FGMP_ERR_INVALID_ARG;
     if (rows <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (!(S > 0.0f) || !(S < INFINITY) || T != T) return FGMP_ERR_INVALID_ARG;
@@ -461,6 +504,7 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
     p.x16 = x16; p.ld16 = ld16;
     if (zero_n < 0 || zero_n > 0x7FFFFFFF || (zero_n > 0 && !zero)) return FGMP_ERR_INVALID_ARG;
     p.zero = zero; p.zero_n = (int)zero_n;
+    p.delta = score_mode == FGMP_SCORE_DELTA;
     if (x16 != nullptr) {
         p.mode = kModeF16;
         if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);

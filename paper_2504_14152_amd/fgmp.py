@@ -50,6 +50,13 @@ def lib() -> ctypes.CDLL:
     L.fgmp_quantize_weights.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i64, f32, f32, vp, sz, vp, vp]
     L.fgmp_quantize_activations.restype = ctypes.c_int
     L.fgmp_quantize_activations.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, sz, vp, vp]
+    L.fgmp_quantize_weights_ex.restype = ctypes.c_int
+    L.fgmp_quantize_weights_ex.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i64, f32, f32, ctypes.c_int, vp, sz, vp, vp]
+    L.fgmp_quantize_activations_ex.restype = ctypes.c_int
+    L.fgmp_quantize_activations_ex.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, ctypes.c_int, vp, sz, vp, vp]
+    L.fgmp_quant_gemm_fused_ex.restype = ctypes.c_int
+    L.fgmp_quant_gemm_fused_ex.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, ctypes.c_int, vp, i64, vp, i64,
+                                           vp, sz, vp]
     L.fgmp_gemm.restype = ctypes.c_int
     L.fgmp_gemm.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, sz, vp]
     L.fgmp_quant_gemm_fused.restype = ctypes.c_int
@@ -127,29 +134,42 @@ def _alloc_packed(rows: int, K: int, device) -> Packed:
     return Packed(torch.empty(n, dtype=torch.uint8, device=device), rows, K)
 
 
+SCORE_MODES = {"nvfp4_error": 0, "delta": 1}   # fgmp_score_mode_t
+
+
 def quantize_weights(W: torch.Tensor, fisher: torch.Tensor, threshold: float, tensor_scale: float,
-                     want_scores: bool = False, out: Packed | None = None):
+                     want_scores: bool = False, out: Packed | None = None, score_mode: str | None = None):
     _require_cuda(W, fisher)
     N, K = W.shape
     ldf = 0 if fisher.dim() == 1 else fisher.stride(0)
     out = out or _alloc_packed(N, K, W.device)
     scores = torch.empty((N, K // 16), dtype=torch.float32, device=W.device) if want_scores else None
-    rc = lib().fgmp_quantize_weights(_ptr(W), _dtype_code(W), N, K, W.stride(0), _ptr(fisher), ldf,
-                                     float(threshold), float(tensor_scale), _ptr(out.buf), out.buf.numel(),
-                                     _ptr(scores), _stream())
+    if score_mode is None:
+        rc = lib().fgmp_quantize_weights(_ptr(W), _dtype_code(W), N, K, W.stride(0), _ptr(fisher), ldf,
+                                         float(threshold), float(tensor_scale), _ptr(out.buf), out.buf.numel(),
+                                         _ptr(scores), _stream())
+    else:
+        rc = lib().fgmp_quantize_weights_ex(_ptr(W), _dtype_code(W), N, K, W.stride(0), _ptr(fisher), ldf,
+                                            float(threshold), float(tensor_scale), SCORE_MODES[score_mode],
+                                            _ptr(out.buf), out.buf.numel(), _ptr(scores), _stream())
     _check(rc, "fgmp_quantize_weights")
     return (out, scores) if want_scores else out
 
 
 def quantize_activations(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, tensor_scale: float,
-                         want_scores: bool = False, out: Packed | None = None):
+                         want_scores: bool = False, out: Packed | None = None, score_mode: str | None = None):
     _require_cuda(X, fisher_k)
     M, K = X.shape
     out = out or _alloc_packed(M, K, X.device)
     scores = torch.empty((M, K // 16), dtype=torch.float32, device=X.device) if want_scores else None
-    rc = lib().fgmp_quantize_activations(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
-                                         float(threshold), float(tensor_scale), _ptr(out.buf),
-                                         out.buf.numel(), _ptr(scores), _stream())
+    if score_mode is None:
+        rc = lib().fgmp_quantize_activations(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                             float(threshold), float(tensor_scale), _ptr(out.buf),
+                                             out.buf.numel(), _ptr(scores), _stream())
+    else:
+        rc = lib().fgmp_quantize_activations_ex(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                                float(threshold), float(tensor_scale), SCORE_MODES[score_mode],
+                                                _ptr(out.buf), out.buf.numel(), _ptr(scores), _stream())
     _check(rc, "fgmp_quantize_activations")
     return (out, scores) if want_scores else out
 
@@ -169,7 +189,8 @@ def gemm(pX: Packed, pW: Packed, out: torch.Tensor | None = None, workspace: tor
 
 
 def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, scale_x: float, pW: Packed,
-                     out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+                     out: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                     score_mode: str | None = None):
     _require_cuda(X, fisher_k)
     M, K = X.shape
     if K != pW.K:
@@ -178,9 +199,14 @@ def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, 
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=X.device)
     if workspace is None:
         workspace = torch.empty(workspace_bytes(M, N, K), dtype=torch.uint8, device=X.device)
-    rc = lib().fgmp_quant_gemm_fused(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
-                                     float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(Y), Y.stride(0),
-                                     _ptr(workspace), workspace.numel(), _stream())
+    if score_mode is None:
+        rc = lib().fgmp_quant_gemm_fused(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                         float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(Y), Y.stride(0),
+                                         _ptr(workspace), workspace.numel(), _stream())
+    else:
+        rc = lib().fgmp_quant_gemm_fused_ex(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                            float(threshold), float(scale_x), SCORE_MODES[score_mode], _ptr(pW.buf),
+                                            N, _ptr(Y), Y.stride(0), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "fgmp_quant_gemm_fused")
     return Y
 

@@ -202,6 +202,75 @@ def test_quantize_dequantize_f16_is_exact(rows, K, p, scale_div):
     assert (got[r8:] == 7.0).all() and (got[:, k128:] == 7.0).all()
 
 
+# ------------------------------------------------------------------ Eq. 8 score mode
+
+@pytest.mark.parametrize("rows,K,bf16,p,scale_div", [(16, 256, False, 0.1, 1.0), (67, 1040, True, 0.3, 1.0),
+                                                      (256, 4096, True, 0.1, 1.0), (40, 400, False, 0.5, 8.0),
+                                                      (9, 16, True, 1.0, 1.0), (24, 128, False, 0.0, 1.0)])
+def test_quantize_activations_delta_score(rows, K, bf16, p, scale_div):
+    """Score = sum F (Q_NVFP4(x) - Q_FP8(x))^2: scores, decisions and codes bit-exact,
+    including a tensor scale below amax / 448 (FP8 reconstruction saturates)."""
+    _say(f"delta score acts {rows}x{K} bf16={bf16} p={p} S/={scale_div}")
+    x = synth.activations(rows, K, 12, 81, outlier_count=max(1, K // 100))
+    f = synth.fisher_per_channel(K, 12, 82)
+    if bf16:
+        xd, xref = _to_dev_bf16(x)
+    else:
+        xd, xref = torch.from_numpy(x).to(DEV), x
+    S = float(synth.default_tensor_scale(xref)) / scale_div
+    T = orc.threshold(orc.quantize(xref, f, np.inf, S, score_mode="delta")["scores"], p)
+    want = orc.quantize(xref, f, T, S, score_mode="delta")
+    pk, scores = fgmp.quantize_activations(xd, torch.from_numpy(f).to(DEV), T, S, want_scores=True,
+                                           score_mode="delta")
+    _assert_quant_equal(pk, scores, want, "delta acts")
+    # the plain entry point and the explicit default mode are the same computation
+    a = fgmp.quantize_activations(xd, torch.from_numpy(f).to(DEV), T, S)
+    b = fgmp.quantize_activations(xd, torch.from_numpy(f).to(DEV), T, S, score_mode="nvfp4_error")
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(a), fgmp.unpack_canonical(b)))
+
+
+@pytest.mark.parametrize("N,K,per_elem,p", [(77, 304, True, 0.3), (512, 1024, False, 0.1), (64, 128, True, 1.0)])
+def test_quantize_weights_delta_score(N, K, per_elem, p):
+    _say(f"delta score weights {N}x{K} per_elem={per_elem} p={p}")
+    w = synth.weights(N, K, 13, 83)
+    f = synth.fisher_per_element(N, K, 13, 84) if per_elem else np.ones(K, dtype=np.float32)   # ones: Eq. 12
+    wd, wref = _to_dev_bf16(w)
+    S = float(synth.default_tensor_scale(wref))
+    T = orc.threshold(orc.quantize(wref, f, np.inf, S, score_mode="delta")["scores"], p)
+    want = orc.quantize(wref, f, T, S, score_mode="delta")
+    pk, scores = fgmp.quantize_weights(wd, torch.from_numpy(f).to(DEV), T, S, want_scores=True, score_mode="delta")
+    _assert_quant_equal(pk, scores, want, "delta weights")
+    assert fgmp.packed_info(pk)["n_fp8_blocks"] == int(want["mask"].sum())
+
+
+@pytest.mark.parametrize("M,K,N", [(200, 304, 136), (8, 1024, 72)])
+def test_fused_delta_score(M, K, N):
+    """Fused call with Eq. 8 scoring (prefill and decode shape) against the oracle."""
+    _say(f"fused delta M={M} K={K} N={N}")
+    x = synth.activations(M, K, 14, 85)
+    w = synth.weights(N, K, 14, 86)
+    fx, fw = synth.fisher_per_channel(K, 14, 87), synth.fisher_per_channel(K, 14, 88)
+    xd, xref = _to_dev_bf16(x)
+    wd, wref = _to_dev_bf16(w)
+    sx, sw = float(synth.default_tensor_scale(xref)), float(synth.default_tensor_scale(wref))
+    Tx = orc.threshold(orc.quantize(xref, fx, np.inf, sx, score_mode="delta")["scores"], 0.2)
+    Tw = orc.threshold(orc.quantize(wref, fw, np.inf, sw, score_mode="delta")["scores"], 0.2)
+    pW = fgmp.quantize_weights(wd, torch.from_numpy(fw).to(DEV), Tw, sw, score_mode="delta")
+    Y = fgmp.quant_gemm_fused(xd, torch.from_numpy(fx).to(DEV), Tx, sx, pW, score_mode="delta")
+    qx = orc.quantize(xref, fx, Tx, sx, score_mode="delta")
+    qw = orc.quantize(wref, fw, Tw, sw, score_mode="delta")
+    want, tol = orc.gemm(orc.dequantize(qx["codes"], qx["scales"], qx["mask"]), sx,
+                         orc.dequantize(qw["codes"], qw["scales"], qw["mask"]), sw)
+    err = np.abs(Y.cpu().numpy().astype(np.float64) - want)
+    assert np.all(err <= tol)
+    # an unknown mode is rejected before anything is launched
+    buf = torch.empty(fgmp.packed_bytes(M, K), dtype=torch.uint8, device=DEV)
+    fxd = torch.from_numpy(fx).to(DEV)
+    rc = fgmp.lib().fgmp_quantize_activations_ex(xd.data_ptr(), 1, M, K, K, fxd.data_ptr(), 0.0, 1.0, 7,
+                                                 buf.data_ptr(), buf.numel(), None, None)
+    assert rc == -1
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)
