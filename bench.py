@@ -207,6 +207,16 @@ def main() -> int:
         extra["act_quant_16384x8192"] = {"ms": round(ms_q, 4), "GBps": round(gbps, 1),
                                          "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
                                          "algorithmic_bytes": int(qbytes)}
+        # the same pass with the Eq. 8 score (error increase of NVFP4 over FP8): threshold recalibrated for 10%
+        _, sc = fgmp.quantize_activations(xqd, fq, float("inf"), sq, want_scores=True, score_mode="delta")
+        Tqd = fgmp.threshold_for_fraction(sc, P_FP8)
+        del sc
+        ms_qd = timed(lambda: fgmp.quantize_activations(xqd, fq, Tqd, sq, out=pq, score_mode="delta"), 20, 3)
+        extra["act_quant_16384x8192_eq8_score"] = {"ms": round(ms_qd, 4),
+                                                   "GBps": round(qbytes / (ms_qd * 1e-3) / 1e9, 1),
+                                                   "frac_hbm_peak": round(qbytes / (ms_qd * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                                                   "fp8_fraction": round(fgmp.packed_info(pq)["n_fp8_blocks"] /
+                                                                         (Mq * Kq // 16), 4)}
         del xqd, pq
         # decode shapes (configs[3]): M tokens against packed weights of the four Llama-2-7B linears; a step
         # is fgmp_quant_gemm_fused (two kernels: quantizer, weight-streaming GEMM).
