@@ -160,21 +160,61 @@ void fgmp_oracle_e4m3_encode_many(const float *r, int64_t n, uint8_t *out)
  * FP8, Q_NVFP4(v) - Q_FP8(v) [Eq. 7, Eq. 8]; with the weights set to one, or
  * to the other operand's mean squared channel magnitude, the same sum is the
  * "quantization error" and "output error" baseline policy [Sec. 3.4, Eq. 12, Eq. 13]. */
+/* Sensitivity-weighted NVFP4 error of one block under the block scale code sc
+ * [the objective of Eq. 11]: the same arithmetic as the scoring below. */
+static float nvfp4_error_with_scale(const float *x, const float *f, float S,
+                                    uint8_t sc)
+{
+    const float d = fgmp_oracle_e4m3_decode(sc) * S;
+    float inv_d = 0.0f;
+    if (sc != 0) inv_d = 1.0f / d;
+    float lvl[FGMP_ORACLE_BLOCK];
+    for (int i = 0; i < FGMP_ORACLE_BLOCK; ++i) {
+        float xhat = 0.0f;
+        if (sc != 0)
+            xhat = fgmp_oracle_e2m1_decode(fgmp_oracle_e2m1_encode(x[i] * inv_d)) * d;
+        float e = x[i] - xhat;
+        float e2 = e * e;
+        lvl[i] = e2 * f[i];
+    }
+    for (int width = FGMP_ORACLE_BLOCK; width > 1; width /= 2)
+        for (int i = 0; i < width / 2; ++i) lvl[i] = lvl[2 * i] + lvl[2 * i + 1];
+    return lvl[0];
+}
+
+/* Sensitivity-weighted clipping [Sec. 3.3, Eq. 11]: brute force over every
+ * non-negative E4M3 scale code (0 .. 0x7E); the code with the smallest weighted
+ * error wins, the smallest code among equals. */
+static uint8_t clipped_scale(const float *x, const float *f, float S)
+{
+    uint8_t best = 0;
+    float best_err = nvfp4_error_with_scale(x, f, S, 0);
+    for (int sc = 1; sc <= 0x7E; ++sc) {
+        float err = nvfp4_error_with_scale(x, f, S, (uint8_t)sc);
+        if (err < best_err) {
+            best_err = err;
+            best = (uint8_t)sc;
+        }
+    }
+    return best;
+}
+
 static void quantize_block(const float *x, const float *f, float S, float T,
-                           int score_mode, uint8_t *codes, uint8_t *scale,
-                           uint8_t *mask, float *score)
+                           int score_mode, int clip, uint8_t *codes,
+                           uint8_t *scale, uint8_t *mask, float *score)
 {
     const float inv_S = 1.0f / S;
     const float S6 = 6.0f * S; /* largest E2M1 magnitude times the tensor scale */
 
-    /* dynamic-max block scale [Sec. 3.3], stored as E4M3 [Sec. 4] */
+    /* dynamic-max block scale [Sec. 3.3], stored as E4M3 [Sec. 4]; or the
+     * clipped one [Eq. 11] */
     float amax = 0.0f;
     for (int i = 0; i < FGMP_ORACLE_BLOCK; ++i) {
         float a = fabsf(x[i]);
         if (a > amax) amax = a;
     }
     const float u = amax / S6;
-    const uint8_t sc = fgmp_oracle_e4m3_encode(u);
+    const uint8_t sc = clip ? clipped_scale(x, f, S) : fgmp_oracle_e4m3_encode(u);
     const float d = fgmp_oracle_e4m3_decode(sc) * S;
 
     /* NVFP4 values and their reconstruction */
@@ -237,10 +277,10 @@ static void quantize_block(const float *x, const float *f, float S, float T,
  * Outputs (row-major, caller-allocated): codes rows*K bytes, scales / mask /
  * scores rows*K/16 entries.  Returns 0, or -1 on a bad argument (null pointer,
  * non-positive size, K not a multiple of 16, non-finite input or scale). */
-int fgmp_oracle_quantize_mode(const float *x, int64_t rows, int64_t K, int64_t ldx,
-                              const float *fisher, int64_t ld_fisher, float T,
-                              float S, int score_mode, uint8_t *codes,
-                              uint8_t *scales, uint8_t *mask, float *scores)
+static int quantize_tensor(const float *x, int64_t rows, int64_t K, int64_t ldx,
+                           const float *fisher, int64_t ld_fisher, float T,
+                           float S, int score_mode, int clip, uint8_t *codes,
+                           uint8_t *scales, uint8_t *mask, float *scores)
 {
     if (!x || !fisher || !codes || !scales || !mask || !scores) return -1;
     if (score_mode != 0 && score_mode != 1) return -1;
@@ -256,13 +296,35 @@ int fgmp_oracle_quantize_mode(const float *x, int64_t rows, int64_t K, int64_t l
                               b * FGMP_ORACLE_BLOCK;
             for (int i = 0; i < FGMP_ORACLE_BLOCK; ++i)
                 if (!isfinite(xb[i]) || !isfinite(fb[i])) bad = 1;
-            quantize_block(xb, fb, S, T, score_mode,
+            quantize_block(xb, fb, S, T, score_mode, clip,
                            codes + r * K + b * FGMP_ORACLE_BLOCK,
                            scales + r * nb + b, mask + r * nb + b,
                            scores + r * nb + b);
         }
     }
     return bad ? -1 : 0;
+}
+
+/* Score selected by score_mode (0: Eq. 6, 1: Eq. 8); dynamic-max block scales. */
+int fgmp_oracle_quantize_mode(const float *x, int64_t rows, int64_t K, int64_t ldx,
+                              const float *fisher, int64_t ld_fisher, float T,
+                              float S, int score_mode, uint8_t *codes,
+                              uint8_t *scales, uint8_t *mask, float *scores)
+{
+    return quantize_tensor(x, rows, K, ldx, fisher, ld_fisher, T, S, score_mode, 0,
+                           codes, scales, mask, scores);
+}
+
+/* Offline weight quantization with sensitivity-weighted clipping of the block
+ * scales [Sec. 3.3, Eq. 11]; the score of a block is its weighted NVFP4 error
+ * under the chosen scale [Eq. 6]. */
+int fgmp_oracle_quantize_clip(const float *x, int64_t rows, int64_t K, int64_t ldx,
+                              const float *fisher, int64_t ld_fisher, float T,
+                              float S, uint8_t *codes, uint8_t *scales,
+                              uint8_t *mask, float *scores)
+{
+    return quantize_tensor(x, rows, K, ldx, fisher, ld_fisher, T, S, 0, 1, codes,
+                           scales, mask, scores);
 }
 
 /* The default scoring [Eq. 6]. */

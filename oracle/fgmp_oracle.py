@@ -59,6 +59,9 @@ def _load():
     lib.fgmp_oracle_quantize_mode.restype = ctypes.c_int
     lib.fgmp_oracle_quantize_mode.argtypes = [f32p, i64, i64, i64, f32p, i64, ctypes.c_float,
                                               ctypes.c_float, ctypes.c_int, u8p, u8p, u8p, f32p]
+    lib.fgmp_oracle_quantize_clip.restype = ctypes.c_int
+    lib.fgmp_oracle_quantize_clip.argtypes = [f32p, i64, i64, i64, f32p, i64, ctypes.c_float,
+                                              ctypes.c_float, u8p, u8p, u8p, f32p]
     lib.fgmp_oracle_dequantize.restype = ctypes.c_int
     lib.fgmp_oracle_dequantize.argtypes = [u8p, u8p, u8p, i64, i64, f64p]
     lib.fgmp_oracle_gemm.restype = ctypes.c_int
@@ -105,9 +108,11 @@ def e4m3_encode(r) -> np.ndarray:
 SCORE_MODES = {"nvfp4_error": 0, "delta": 1}
 
 
-def quantize(x: np.ndarray, fisher: np.ndarray, threshold: float, scale: float, score_mode: str = "nvfp4_error"):
+def quantize(x: np.ndarray, fisher: np.ndarray, threshold: float, scale: float, score_mode: str = "nvfp4_error",
+             clip: bool = False):
     """Quantize a rows x K fp32 tensor.  fisher is (K,) per channel or (rows, K)
     per element.  score_mode: "nvfp4_error" (Eq. 6) or "delta" (Eq. 8).
+    clip: choose each block scale by sensitivity-weighted clipping (Eq. 11).
     Returns dict(codes, scales, mask, scores)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     fisher = np.ascontiguousarray(fisher, dtype=np.float32)
@@ -123,6 +128,17 @@ def quantize(x: np.ndarray, fisher: np.ndarray, threshold: float, scale: float, 
     scales = np.empty((rows, nb), dtype=np.uint8)
     mask = np.empty((rows, nb), dtype=np.uint8)
     scores = np.empty((rows, nb), dtype=np.float32)
+    if clip:
+        if score_mode != "nvfp4_error":
+            raise ValueError("clipping is defined with the NVFP4-error score")
+        rc = _load().fgmp_oracle_quantize_clip(_ptr(x, ctypes.c_float), rows, K, K,
+                                               _ptr(fisher, ctypes.c_float), ldf,
+                                               ctypes.c_float(threshold), ctypes.c_float(scale),
+                                               _ptr(codes, ctypes.c_uint8), _ptr(scales, ctypes.c_uint8),
+                                               _ptr(mask, ctypes.c_uint8), _ptr(scores, ctypes.c_float))
+        if rc != 0:
+            raise ValueError("fgmp_oracle_quantize_clip: bad argument or non-finite input")
+        return {"codes": codes, "scales": scales, "mask": mask, "scores": scores}
     rc = _load().fgmp_oracle_quantize_mode(_ptr(x, ctypes.c_float), rows, K, K,
                                            _ptr(fisher, ctypes.c_float), ldf,
                                            ctypes.c_float(threshold), ctypes.c_float(scale),

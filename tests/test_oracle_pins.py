@@ -241,6 +241,88 @@ def test_delta_mode_changes_only_scores_and_decisions():
     assert np.array_equal(m0, m1) and abs(m0.mean() - 0.2) < 0.01
 
 
+# ---------------------------------------------------------------- Eq. 11 clipping
+
+def _nvfp4_error_fp64(xb, fb, d):
+    """sum F (x - Q(x))^2 for one block and one scale step d, in fp64, with an
+    E2M1 rounding written here from the format table (nearest, ties to the even code)."""
+    mags = np.array(E2M1, dtype=np.float64)
+    if d == 0.0:
+        return float(np.sum(fb * xb * xb))
+    r = np.abs(xb) / d
+    dist = np.abs(r[:, None] - mags[None, :])
+    best = dist.min(axis=1, keepdims=True)
+    cand = np.where(dist == best, np.arange(8)[None, :], 99)
+    lo = cand.min(axis=1)
+    hi = np.where(cand == 99, -1, cand).max(axis=1)
+    code = np.where(lo % 2 == 0, lo, hi)          # a tie is between neighbours: take the even one
+    xhat = np.sign(xb) * mags[code] * d
+    return float(np.sum(fb * (xb - xhat) ** 2))
+
+
+def test_clipped_scales_minimize_the_weighted_error():
+    """Eq. 11 by brute force in fp64 over all 127 E4M3 scale values, on sampled
+    blocks: the oracle's error under its chosen scale equals the minimum, and it
+    never exceeds the dynamic-max error."""
+    w = synth.weights(32, 256, 4, 31)
+    f = synth.fisher_per_element(32, 256, 4, 32)
+    S = float(synth.default_tensor_scale(w))
+    dyn = orc.quantize(w, f, np.inf, S)
+    clip = orc.quantize(w, f, np.inf, S, clip=True)
+    assert np.all(clip["scores"] <= dyn["scores"])
+    assert clip["scores"].sum() < 0.8 * dyn["scores"].sum()        # it does something on Gaussian weights
+    e4 = _torch_e4m3_decode_all().astype(np.float64)[:127]
+    S64 = np.float64(np.float32(S))
+    rng = np.random.default_rng(0)
+    for r, b in zip(rng.integers(0, 32, 40), rng.integers(0, 16, 40)):
+        xb = w[r, 16 * b:16 * b + 16].astype(np.float64)
+        fb = f[r, 16 * b:16 * b + 16].astype(np.float64)
+        errs = np.array([_nvfp4_error_fp64(xb, fb, e4[c] * S64) for c in range(127)])
+        np.testing.assert_allclose(clip["scores"][r, b], errs.min(), rtol=1e-5)
+        # the stored scale reproduces that error, and the stored codes are that scale's quantization
+        np.testing.assert_allclose(errs[clip["scales"][r, b]], errs.min(), rtol=1e-5)
+        xhat = orc.dequantize(clip["codes"][r:r + 1, 16 * b:16 * b + 16], clip["scales"][r:r + 1, b:b + 1],
+                              clip["mask"][r:r + 1, b:b + 1])[0] * S64
+        np.testing.assert_allclose(np.sum(fb * (xb - xhat) ** 2), errs.min(), rtol=1e-5)
+
+
+def test_clipping_trades_an_insensitive_outlier_for_resolution():
+    """One large element with a negligible sensitivity next to fifteen small,
+    sensitive ones: dynamic max spends the range on the outlier, Eq. 11 does not."""
+    x = np.full((1, 16), 0.7, dtype=np.float32)
+    x[0, 5] = 12.0
+    f = np.ones((1, 16), dtype=np.float32)
+    f[0, 5] = 1e-6
+    dyn = orc.quantize(x, f, np.inf, 1.0)
+    clip = orc.quantize(x, f, np.inf, 1.0, clip=True)
+    assert orc.e4m3_decode(int(dyn["scales"][0, 0])) == 2.0            # 12 / 6
+    assert clip["scales"][0, 0] < dyn["scales"][0, 0]
+    assert clip["scores"][0, 0] < 0.05 * dyn["scores"][0, 0]
+    # the outlier saturates at 6 times the clipped scale
+    assert clip["codes"][0, 5] == 7
+    # an all-zero block keeps scale code 0, a block that dynamic max represents exactly stays exact
+    z = orc.quantize(np.zeros((1, 16), np.float32), f, np.inf, 1.0, clip=True)
+    assert z["scales"][0, 0] == 0 and z["scores"][0, 0] == 0.0
+    exact = (np.array(E2M1 + E2M1, dtype=np.float32) * 0.25)[None, :]
+    e = orc.quantize(exact, f, np.inf, 1.0, clip=True)
+    assert e["scores"][0, 0] == 0.0
+
+
+def test_clipping_invariants():
+    w = synth.weights(16, 128, 6, 33)
+    f = synth.fisher_per_element(16, 128, 6, 34)
+    S = float(synth.default_tensor_scale(w))
+    a = orc.quantize(w, f, np.inf, S, clip=True)
+    b = orc.quantize(w, 4.0 * f, np.inf, S, clip=True)              # weights scaled by a power of two
+    c = orc.quantize(2.0 * w, f, np.inf, 2.0 * S, clip=True)        # tensor and its scale scaled together
+    for other in (b, c):
+        assert np.array_equal(a["codes"], other["codes"]) and np.array_equal(a["scales"], other["scales"])
+    assert np.array_equal(b["scores"], 4.0 * a["scores"]) and np.array_equal(c["scores"], 4.0 * a["scores"])
+    # the precision decision uses the clipped error: fewer blocks exceed a fixed threshold
+    T = orc.threshold(orc.quantize(w, f, np.inf, S)["scores"], 0.3)
+    assert orc.quantize(w, f, T, S, clip=True)["mask"].sum() < orc.quantize(w, f, T, S)["mask"].sum()
+
+
 def test_block_scale_is_dynamic_max():
     """The stored block scale is the E4M3 code nearest to amax / (6 S)."""
     x, f, S = _random_case()
