@@ -161,6 +161,21 @@ fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M
                                        int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Offline weight quantization with sensitivity-weighted clipping (Sec. 3.3, Eq. 11): the E4M3
+ * scale of every block is the one, among all 127 non-negative E4M3 values, that minimizes
+ * sum_i F_i (w_i - Q_s(w_i))^2 (the smallest such code if several tie) instead of the dynamic-max
+ * scale; the block's score (Eq. 6) and the FP8/FP4 decision then use that scale.  Everything else as
+ * fgmp_quantize_weights.
+ *   workspace  device scratch, at least N*K/16 bytes (the chosen scale codes); contents undefined after
+ * Errors: as fgmp_quantize_weights; FGMP_ERR_BUFFER_TOO_SMALL for the workspace.
+ */
+fgmp_status_t fgmp_quantize_weights_clip(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
+                                         const float *fisher, int64_t ld_fisher, float threshold,
+                                         float tensor_scale, void *packed_W, size_t packed_bytes,
+                                         float *scores_out, void *workspace, size_t workspace_bytes,
+                                         void *stream);
+
+/*
  * Expand a packed tensor to layout-independent arrays (for tests and tools):
  *   codes   rows*K bytes: E2M1 code 0..15 (FP4 block) or E4M3 byte (FP8 block)
  *   scales  rows*K/16 bytes: E4M3 block scale, 0 for FP8 blocks

@@ -86,6 +86,21 @@ fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M
                       workspace_bytes, as_stream(stream), (int)score_mode);
 }
 
+fgmp_status_t fgmp_quantize_weights_clip(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
+                                         const float *fisher, int64_t ld_fisher, float threshold,
+                                         float tensor_scale, void *packed_W, size_t packed_bytes,
+                                         float *scores_out, void *workspace, size_t workspace_bytes,
+                                         void *stream)
+{
+    if (!workspace) return FGMP_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    if (workspace_bytes < (size_t)(N * (K / kBlock))) return FGMP_ERR_BUFFER_TOO_SMALL;
+    return quantize_tensor(W, dt, N, K, ldw, fisher, ld_fisher, threshold, tensor_scale, packed_W,
+                           packed_bytes, scores_out, /*compact=*/true, as_stream(stream), nullptr, 0, nullptr, 0,
+                           FGMP_SCORE_NVFP4_ERROR, static_cast<uint8_t *>(workspace));
+}
+
 fgmp_status_t fgmp_unpack_canonical(const void *packed, int64_t rows, int64_t K, uint8_t *codes,
                                     uint8_t *scales, uint8_t *mask, void *stream)
 {

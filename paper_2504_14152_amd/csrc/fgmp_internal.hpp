@@ -22,7 +22,8 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
                               _Float16 *x16 = nullptr, int64_t ld16 = 0, uint32_t *zero = nullptr,
-                              int64_t zero_n = 0, int score_mode = FGMP_SCORE_NVFP4_ERROR);
+                              int64_t zero_n = 0, int score_mode = FGMP_SCORE_NVFP4_ERROR,
+                              uint8_t *clip_scales = nullptr);
 fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
                             uint8_t *mask, hipStream_t st);
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,

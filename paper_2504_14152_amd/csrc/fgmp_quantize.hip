@@ -47,6 +47,7 @@ struct QuantParams {
     uint32_t *zero;        // words cleared by the first workgroup (counters of the kernel that follows)
     int zero_n;
     bool delta;            // Eq. 8 scoring (see quantize_kernel)
+    const uint8_t *sc_override;   // block scale codes chosen beforehand (clipping), [rows][nb]; or nullptr: dynamic max
 };
 
 // kModeF16 writes, instead of the packed planes, the FP16 value of every stored
@@ -199,7 +200,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(x[i]));
         const float u = amax / S6;
-        const uint32_t sc = enc_e4m3<kHW>(u);
+        uint32_t sc = enc_e4m3<kHW>(u);
+        if (p.sc_override != nullptr) sc = valid ? (uint32_t)p.sc_override[row * p.nb + kb] : 0u;
         const float d = e4m3_decode_int(sc) * p.S;
         const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
 
@@ -354,6 +356,73 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
     process(rt0 + 4 * (int64_t)(n_it - 1), cur);
 }
 
+// Sensitivity-weighted clipping (Sec. 3.3, Eq. 11): for every block, the E4M3 scale code (0 .. 0x7E)
+// whose NVFP4 quantization has the smallest weighted error -- brute force, candidates in ascending
+// order, a later candidate wins only with a strictly smaller error.  One block per lane; the error of
+// a candidate is computed exactly as quantize_kernel computes a block's score.  Offline (weights).
+template <typename Tin, bool kPerElem, bool kHW>
+__global__ __launch_bounds__(256) void clip_scales_kernel(QuantParams p, uint8_t *sc_out)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t kt = blockIdx.x;
+    const int64_t kb = kt * kTileBlocks + (lane & 7);
+    const int64_t rt = (int64_t)blockIdx.y * 4 + wave;
+    const int64_t row = rt * kTileRows + (lane >> 3);
+    if (rt >= p.n_rt || kb >= p.nb || row >= p.rows) return;
+    const Tin *X = static_cast<const Tin *>(p.X);
+    RawBlock<Tin> raw;
+    load_raw(X + row * p.ldx + kb * kBlock, raw);
+    float x[16], f[16];
+    widen(raw, x);
+    load16(p.fisher + (kPerElem ? row * p.ld_fisher : 0) + kb * kBlock, f);
+
+    auto error_with = [&](uint32_t sc) {
+        const float d = e4m3_decode_int(sc) * p.S;
+        const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
+        float t[16];
+        if constexpr (kHW) {
+            uint32_t q[2] = {0u, 0u};
+#define FGMP_ENC(W, B, I) q[W] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q[W], x[I] * inv_d, x[I + 1] * inv_d, 1.0f, B)
+            FGMP_ENC(0, 0, 0); FGMP_ENC(0, 1, 2); FGMP_ENC(0, 2, 4); FGMP_ENC(0, 3, 6);
+            FGMP_ENC(1, 0, 8); FGMP_ENC(1, 1, 10); FGMP_ENC(1, 2, 12); FGMP_ENC(1, 3, 14);
+#undef FGMP_ENC
+#define FGMP_ERR(W, B, I)                                                              \
+    {                                                                                  \
+        const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);    \
+        const float e0 = x[I] - v[0] * d, e1 = x[I + 1] - v[1] * d;                    \
+        t[I] = (e0 * e0) * f[I];                                                       \
+        t[I + 1] = (e1 * e1) * f[I + 1];                                               \
+    }
+            FGMP_ERR(0, 0, 0) FGMP_ERR(0, 1, 2) FGMP_ERR(0, 2, 4) FGMP_ERR(0, 3, 6)
+            FGMP_ERR(1, 0, 8) FGMP_ERR(1, 1, 10) FGMP_ERR(1, 2, 12) FGMP_ERR(1, 3, 14)
+#undef FGMP_ERR
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float e = x[i] - e2m1_decode_int(e2m1_encode_int(x[i] * inv_d)) * d;
+                t[i] = (e * e) * f[i];
+            }
+        }
+#pragma unroll
+        for (int w = 16; w > 1; w >>= 1)
+#pragma unroll
+            for (int i = 0; i < w / 2; ++i) t[i] = t[2 * i] + t[2 * i + 1];
+        return t[0];
+    };
+    uint32_t best = 0u;
+    float best_err = error_with(0u);
+#pragma unroll 1
+    for (uint32_t sc = 1u; sc <= 0x7Eu; ++sc) {
+        const float err = error_with(sc);
+        if (err < best_err) {
+            best_err = err;
+            best = sc;
+        }
+    }
+    sc_out[row * p.nb + kb] = (uint8_t)best;
+}
+
 // Exclusive prefix sum over the per-tile FP8 counts in plane T (one workgroup),
 // then the header fields that depend on the total.
 __global__ __launch_bounds__(1024) void scan_tiles_kernel(uint32_t *T, int64_t n_tiles, PackedHeader *hdr,
@@ -461,7 +530,8 @@ static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipS
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
-                              _Float16 *x16, int64_t ld16, uint32_t *zero, int64_t zero_n, int score_mode)
+                              _Float16 *x16, int64_t ld16, uint32_t *zero, int64_t zero_n, int score_mode,
+                              uint8_t *clip_scales)
 {
     if (score_mode != FGMP_SCORE_NVFP4_ERROR && score_mode != FGMP_SCORE_DELTA) return FGMP_ERR_INVALID_ARG;
     if (!X || !fisher || (!packed && !x16)) return FGMP_ERR_INVALID_ARG;
@@ -505,6 +575,21 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
     if (zero_n < 0 || zero_n > 0x7FFFFFFF || (zero_n > 0 && !zero)) return FGMP_ERR_INVALID_ARG;
     p.zero = zero; p.zero_n = (int)zero_n;
     p.delta = score_mode == FGMP_SCORE_DELTA;
+    p.sc_override = clip_scales;
+    if (clip_scales != nullptr) {
+        // clipping is defined with the NVFP4-error score; the scale search runs first, on the same stream
+        if (p.delta || x16 != nullptr) return FGMP_ERR_UNSUPPORTED;
+        const int64_t gy4 = (l.n_rt + 3) / 4;
+        if (gy4 > 65535) return FGMP_ERR_UNSUPPORTED;
+        const dim3 cgrid((unsigned)l.n_kt, (unsigned)gy4);
+        if (dt == FGMP_F32) {
+            if (per_elem) hipLaunchKernelGGL((clip_scales_kernel<float, true, kUseHwCvt>), cgrid, dim3(256), 0, st, p, clip_scales);
+            else hipLaunchKernelGGL((clip_scales_kernel<float, false, kUseHwCvt>), cgrid, dim3(256), 0, st, p, clip_scales);
+        } else {
+            if (per_elem) hipLaunchKernelGGL((clip_scales_kernel<uint16_t, true, kUseHwCvt>), cgrid, dim3(256), 0, st, p, clip_scales);
+            else hipLaunchKernelGGL((clip_scales_kernel<uint16_t, false, kUseHwCvt>), cgrid, dim3(256), 0, st, p, clip_scales);
+        }
+    }
     if (x16 != nullptr) {
         p.mode = kModeF16;
         if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);

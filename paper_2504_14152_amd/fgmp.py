@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
     L.fgmp_quant_gemm_fused_ex.restype = ctypes.c_int
     L.fgmp_quant_gemm_fused_ex.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, ctypes.c_int, vp, i64, vp, i64,
                                            vp, sz, vp]
+    L.fgmp_quantize_weights_clip.restype = ctypes.c_int
+    L.fgmp_quantize_weights_clip.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i64, f32, f32, vp, sz, vp, vp, sz, vp]
     L.fgmp_gemm.restype = ctypes.c_int
     L.fgmp_gemm.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, sz, vp]
     L.fgmp_quant_gemm_fused.restype = ctypes.c_int
@@ -153,6 +155,22 @@ def quantize_weights(W: torch.Tensor, fisher: torch.Tensor, threshold: float, te
                                             float(threshold), float(tensor_scale), SCORE_MODES[score_mode],
                                             _ptr(out.buf), out.buf.numel(), _ptr(scores), _stream())
     _check(rc, "fgmp_quantize_weights")
+    return (out, scores) if want_scores else out
+
+
+def quantize_weights_clip(W: torch.Tensor, fisher: torch.Tensor, threshold: float, tensor_scale: float,
+                          want_scores: bool = False, out: Packed | None = None):
+    """quantize_weights with the block scales chosen by sensitivity-weighted clipping (Eq. 11)."""
+    _require_cuda(W, fisher)
+    N, K = W.shape
+    ldf = 0 if fisher.dim() == 1 else fisher.stride(0)
+    out = out or _alloc_packed(N, K, W.device)
+    scores = torch.empty((N, K // 16), dtype=torch.float32, device=W.device) if want_scores else None
+    ws = torch.empty(N * (K // 16), dtype=torch.uint8, device=W.device)
+    rc = lib().fgmp_quantize_weights_clip(_ptr(W), _dtype_code(W), N, K, W.stride(0), _ptr(fisher), ldf,
+                                          float(threshold), float(tensor_scale), _ptr(out.buf), out.buf.numel(),
+                                          _ptr(scores), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "fgmp_quantize_weights_clip")
     return (out, scores) if want_scores else out
 
 

@@ -271,6 +271,60 @@ def test_fused_delta_score(M, K, N):
     assert rc == -1
 
 
+# ------------------------------------------------------------------ Eq. 11 clipping
+
+@pytest.mark.parametrize("N,K,bf16,per_elem,p", [(64, 256, False, True, 0.1), (77, 304, True, True, 0.3),
+                                                 (256, 1024, True, False, 0.1), (8, 16, False, True, 0.0),
+                                                 (40, 128, True, True, 1.0)])
+def test_quantize_weights_clip(N, K, bf16, per_elem, p):
+    """Sensitivity-weighted clipping: chosen scale codes, codes, scores and decisions bit-exact."""
+    _say(f"clip weights N={N} K={K} bf16={bf16} per_elem={per_elem} p={p}")
+    w = synth.weights(N, K, 15, 91)
+    f = synth.fisher_per_element(N, K, 15, 92) if per_elem else synth.fisher_per_channel(K, 15, 93)
+    if bf16:
+        wd, wref = _to_dev_bf16(w)
+    else:
+        wd, wref = torch.from_numpy(w).to(DEV), w
+    S = float(synth.default_tensor_scale(wref))
+    T = orc.threshold(orc.quantize(wref, f, np.inf, S, clip=True)["scores"], p)
+    want = orc.quantize(wref, f, T, S, clip=True)
+    pk, scores = fgmp.quantize_weights_clip(wd, torch.from_numpy(f).to(DEV), T, S, want_scores=True)
+    _assert_quant_equal(pk, scores, want, "clip weights")
+    info = fgmp.packed_info(pk)
+    assert info["compact"] == 1 and info["n_fp8_blocks"] == int(want["mask"].sum())
+    # clipping changed something relative to dynamic max (except in the all-FP8 case, where no scale is kept)
+    plain = orc.quantize(wref, f, T, S)
+    if p < 1.0 and N * K > 1024:
+        assert (plain["scales"] != want["scales"]).mean() > 0.2
+
+
+def test_gemm_with_clipped_weights():
+    M, K, N = 48, 512, 136
+    _say("gemm with clipped weights")
+    x = synth.activations(M, K, 16, 94)
+    w = synth.weights(N, K, 16, 95)
+    fx, fw = synth.fisher_per_channel(K, 16, 96), synth.fisher_per_element(N, K, 16, 97)
+    xd, xref = _to_dev_bf16(x)
+    wd, wref = _to_dev_bf16(w)
+    sx, sw = float(synth.default_tensor_scale(xref)), float(synth.default_tensor_scale(wref))
+    Tx = orc.threshold(orc.quantize(xref, fx, np.inf, sx)["scores"], 0.1)
+    Tw = orc.threshold(orc.quantize(wref, fw, np.inf, sw, clip=True)["scores"], 0.1)
+    pW = fgmp.quantize_weights_clip(wd, torch.from_numpy(fw).to(DEV), Tw, sw)
+    Y = fgmp.quant_gemm_fused(xd, torch.from_numpy(fx).to(DEV), Tx, sx, pW)
+    qx = orc.quantize(xref, fx, Tx, sx)
+    qw = orc.quantize(wref, fw, Tw, sw, clip=True)
+    want, tol = orc.gemm(orc.dequantize(qx["codes"], qx["scales"], qx["mask"]), sx,
+                         orc.dequantize(qw["codes"], qw["scales"], qw["mask"]), sw)
+    assert np.all(np.abs(Y.cpu().numpy().astype(np.float64) - want) <= tol)
+    # a workspace smaller than one byte per block is refused
+    buf = torch.empty(fgmp.packed_bytes(N, K), dtype=torch.uint8, device=DEV)
+    fwd = torch.from_numpy(fw).to(DEV)
+    ws = torch.empty(N * K // 16, dtype=torch.uint8, device=DEV)
+    rc = fgmp.lib().fgmp_quantize_weights_clip(wd.data_ptr(), 1, N, K, K, fwd.data_ptr(), K, 0.0, sw, buf.data_ptr(),
+                                               buf.numel(), None, ws.data_ptr(), ws.numel() - 1, None)
+    assert rc == -4
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)
