@@ -218,6 +218,16 @@ def main() -> int:
                                                    "fp8_fraction": round(fgmp.packed_info(pq)["n_fp8_blocks"] /
                                                                          (Mq * Kq // 16), 4)}
         del xqd, pq
+        # offline weight quantization of the workload's W with sensitivity-weighted clipping (Eq. 11):
+        # 127 candidate scales per block, about 6 FP32 operations per element and candidate
+        pWc = fgmp.quantize_weights_clip(wd, fwd, Tw, sw)
+        ms_clip = timed(lambda: fgmp.quantize_weights_clip(wd, fwd, Tw, sw, out=pWc), 5, 1)
+        ms_plain = timed(lambda: fgmp.quantize_weights(wd, fwd, Tw, sw, out=pWc), 5, 1)
+        clip_flops = 6.0 * 127 * N * K
+        extra["weight_quant_clip_12288x4096"] = {"ms": round(ms_clip, 3), "ms_without_clipping": round(ms_plain, 3),
+                                                 "fp32_TFLOPs": round(clip_flops / (ms_clip * 1e-3) / 1e12, 1),
+                                                 "frac_fp32_vector_peak": round(clip_flops / (ms_clip * 1e-3) / 1e12 / 157.3, 3)}
+        del pWc
         # decode shapes (configs[3]): M tokens against packed weights of the four Llama-2-7B linears; a step
         # is fgmp_quant_gemm_fused (two kernels: quantizer, weight-streaming GEMM).
         # HBM-cold: the launches rotate over copies of the packed weights that together exceed the
