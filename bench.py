@@ -306,6 +306,63 @@ def main() -> int:
         # MLP prefill shapes (configs[2]); whole fused step, activation quantization included
         extra["prefill_fc1_4096x4096x22016"] = prefill_case(4096, 4096, 22016, P_FP8, P_FP8, "normal", 40)
         extra["prefill_fc2_4096x11008x4096"] = prefill_case(4096, 11008, 4096, P_FP8, P_FP8, "silu_gate", 50)
+    def layer_chain():
+        """The four linears of one Llama-2-7B layer as a chain of fused steps (QKV -> O -> FC1 -> FC2; the
+        attention and the gated activation between them are replaced by taking the leading columns of the
+        previous FP32 output), with ONE threshold for all weight tensors and ONE for all activation tensors
+        (Eq. 10) instead of one per tensor.  Returns timing and the per-layer FP8 fractions (cf. Fig. 7)."""
+        shapes = [("qkv", 4096, 12288), ("o", 4096, 4096), ("fc1", 4096, 22016), ("fc2", 11008, 4096)]
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4242)
+        Ws, Fws, Sws, w_scores = [], [], [], []
+        for li, (_, Kl, Nl) in enumerate(shapes):
+            wl = torch.empty((Nl, Kl), dtype=torch.bfloat16, device=dev)
+            wl.normal_(0.0, 0.02, generator=gen)
+            fwl = torch.from_numpy(synth.fisher_per_channel(Kl, 0, 300 + li)).to(dev)
+            swl = float(wl.abs().max().float()) / 448.0
+            _, scl = fgmp.quantize_weights(wl, fwl, float("inf"), swl, want_scores=True)
+            Ws.append(wl); Fws.append(fwl); Sws.append(swl); w_scores.append(scl)
+        T_w = fgmp.threshold_for_fraction_multi(w_scores, P_FP8)
+        del w_scores
+        pWs = [fgmp.quantize_weights(wl, fwl, T_w, swl) for wl, fwl, swl in zip(Ws, Fws, Sws)]
+        del Ws
+        Fxs = [torch.from_numpy(synth.fisher_per_channel(Kl, 0, 310 + li)).to(dev) for li, (_, Kl, _) in enumerate(shapes)]
+        Ys = [torch.empty((M, Nl), dtype=torch.float32, device=dev) for _, _, Nl in shapes]
+        wss = [torch.empty(fgmp.workspace_bytes(M, Nl, Kl), dtype=torch.uint8, device=dev) for _, Kl, Nl in shapes]
+
+        def layer_input(li):
+            return xd if li == 0 else Ys[li - 1][:, :shapes[li][1]]
+        # calibration pass: per-tensor thresholds, activation scales and scores of every layer input
+        Sxs, x_scores = [], []
+        for li in range(4):
+            cur = layer_input(li)
+            sxl = float(cur.abs().max().float()) / 448.0
+            _, scl = fgmp.quantize_activations(cur, Fxs[li], float("inf"), sxl, want_scores=True)
+            fgmp.quant_gemm_fused(cur, Fxs[li], fgmp.threshold_for_fraction(scl, P_FP8), sxl, pWs[li], out=Ys[li],
+                                  workspace=wss[li])
+            Sxs.append(sxl); x_scores.append(scl)
+        T_x = fgmp.threshold_for_fraction_multi(x_scores, P_FP8)
+        del x_scores
+
+        def chain():
+            for li in range(4):
+                fgmp.quant_gemm_fused(layer_input(li), Fxs[li], T_x, Sxs[li], pWs[li], out=Ys[li], workspace=wss[li])
+        ms_c = timed(chain, 20, 5)
+        fl = sum(2.0 * M * Kl * Nl for _, Kl, Nl in shapes)
+        frac_w, frac_x = {}, {}
+        for li, (name, _, _) in enumerate(shapes):
+            iw = fgmp.packed_info(pWs[li])
+            frac_w[name] = round(iw["n_fp8_blocks"] / iw["n_blocks"], 4)
+            ix = fgmp.packed_info(fgmp.quantize_activations(layer_input(li), Fxs[li], T_x, Sxs[li]))
+            frac_x[name] = round(ix["n_fp8_blocks"] / ix["n_blocks"], 4)
+        return {"ms_per_layer_pass": round(ms_c, 4), "TFLOPs": round(fl / (ms_c * 1e-3) / 1e12, 1),
+                "frac_mfma_peak": round(fl / (ms_c * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS, 4),
+                "fp8_fraction_weights_by_layer": frac_w, "fp8_fraction_activations_by_layer": frac_x,
+                "target_fraction": P_FP8}
+
+    if not args.no_extra:
+        extra["layer_chain_llama2_7b_M4096_global_thresholds"] = layer_chain()
+
     if args.sweep:
         sw_res = {}
         for frac in (0.0, 0.1, 0.2, 0.3, 1.0):

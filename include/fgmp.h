@@ -227,6 +227,16 @@ fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host
 fgmp_status_t fgmp_threshold_for_fraction(const float *scores, int64_t J, double fraction,
                                           float *threshold_host, void *stream);
 
+/* One threshold for several tensors (Eq. 10): the same order statistic taken over
+ * the union of n_tensors score arrays (e.g. the weights, or the activations, of
+ * every layer), so that layers keep different fractions of their blocks in FP8
+ * while the total matches `fraction`.
+ *   scores  host array of n_tensors device pointers; counts  host array of their lengths
+ * Synchronizes `stream`; uses host memory for the union. */
+fgmp_status_t fgmp_threshold_for_fraction_multi(const float *const *scores, const int64_t *counts,
+                                                int32_t n_tensors, double fraction, float *threshold_host,
+                                                void *stream);
+
 /*
  * Conversion self-test hooks: run the library's device-side FP32 -> E2M1
  * (format 0) or FP32 -> E4M3 (format 1) rounding over every non-negative FP32

@@ -74,6 +74,9 @@ def lib() -> ctypes.CDLL:
     L.fgmp_packed_info.argtypes = [vp, ctypes.POINTER(_PackedInfo), vp]
     L.fgmp_threshold_for_fraction.restype = ctypes.c_int
     L.fgmp_threshold_for_fraction.argtypes = [vp, i64, ctypes.c_double, ctypes.POINTER(f32), vp]
+    L.fgmp_threshold_for_fraction_multi.restype = ctypes.c_int
+    L.fgmp_threshold_for_fraction_multi.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.c_int32,
+                                                    ctypes.c_double, ctypes.POINTER(f32), vp]
     L.fgmp_selftest_encode_ranges.restype = ctypes.c_int
     L.fgmp_selftest_encode_ranges.argtypes = [ctypes.c_int, vp, vp, vp, vp]
     L.fgmp_selftest_decode_table.restype = ctypes.c_int
@@ -276,6 +279,19 @@ def threshold_for_fraction(scores: torch.Tensor, fraction: float) -> float:
     out = ctypes.c_float()
     _check(lib().fgmp_threshold_for_fraction(_ptr(s), s.numel(), float(fraction), ctypes.byref(out), _stream()),
            "fgmp_threshold_for_fraction")
+    return float(out.value)
+
+
+def threshold_for_fraction_multi(score_tensors, fraction: float) -> float:
+    """One threshold over several score tensors (a global threshold over layers, Eq. 10)."""
+    flat = [t.contiguous().view(-1) for t in score_tensors]
+    _require_cuda(*flat)
+    n = len(flat)
+    ptrs = (ctypes.c_void_p * n)(*[t.data_ptr() for t in flat])
+    counts = (ctypes.c_int64 * n)(*[t.numel() for t in flat])
+    out = ctypes.c_float()
+    _check(lib().fgmp_threshold_for_fraction_multi(ptrs, counts, n, float(fraction), ctypes.byref(out), _stream()),
+           "fgmp_threshold_for_fraction_multi")
     return float(out.value)
 
 

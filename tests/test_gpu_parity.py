@@ -325,6 +325,41 @@ def test_gemm_with_clipped_weights():
     assert rc == -4
 
 
+# ------------------------------------------------------------------ Eq. 10 global threshold
+
+def test_global_threshold_over_layers():
+    """One threshold over the scores of several tensors (Eq. 10) equals the oracle's
+    order statistic over their union: the total FP8 fraction is the target, the
+    per-tensor fractions differ (layers with larger sensitivities keep more FP8)."""
+    _say("global threshold over 3 tensors")
+    shapes = [(64, 512, 1.0), (96, 256, 4.0), (32, 1024, 0.25)]      # rows, K, sensitivity multiplier
+    dev_scores, ref_scores, cases = [], [], []
+    for i, (rows, K, mult) in enumerate(shapes):
+        x = synth.activations(rows, K, 18, 100 + i)
+        f = (synth.fisher_per_channel(K, 18, 110 + i) * mult).astype(np.float32)
+        S = float(synth.default_tensor_scale(x))
+        xd, fd = torch.from_numpy(x).to(DEV), torch.from_numpy(f).to(DEV)
+        _, sc = fgmp.quantize_activations(xd, fd, np.inf, S, want_scores=True)
+        dev_scores.append(sc)
+        ref_scores.append(orc.quantize(x, f, np.inf, S)["scores"])
+        cases.append((x, f, S, xd, fd))
+    p = 0.2
+    T = fgmp.threshold_for_fraction_multi(dev_scores, p)
+    assert T == orc.threshold(np.concatenate([r.reshape(-1) for r in ref_scores]), p)
+    fractions, n_hi, n_all = [], 0, 0
+    for (x, f, S, xd, fd), ref in zip(cases, ref_scores):
+        pk = fgmp.quantize_activations(xd, fd, T, S)
+        info = fgmp.packed_info(pk)
+        assert info["n_fp8_blocks"] == int((ref > T).sum())
+        fractions.append(info["n_fp8_blocks"] / info["n_blocks"])
+        n_hi += info["n_fp8_blocks"]
+        n_all += info["n_blocks"]
+    assert n_hi == int(p * n_all + 0.5)
+    assert fractions[1] > fractions[0] > fractions[2]
+    # one tensor: the same as the single-tensor helper
+    assert fgmp.threshold_for_fraction_multi(dev_scores[:1], p) == fgmp.threshold_for_fraction(dev_scores[0], p)
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)
