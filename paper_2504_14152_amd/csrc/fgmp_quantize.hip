@@ -9,25 +9,10 @@
 //   score = balanced pairwise tree over t_0..t_15 (adjacent pairs first)
 //   FP8 iff score > T (Sec. 4.2); FP8 codes c_i = E4M3(x_i * (1 / S))  (Sec. 5.1)
 #include "fgmp_internal.hpp"
+#include "fgmp_quant_block.hpp"
 
 namespace fgmp {
 
-template <bool kHW> __device__ __forceinline__ uint32_t enc_e4m3(float r)
-{
-    if constexpr (kHW) return e4m3_encode_pair_hw(r, 0.0f) & 0xFFu;
-    else return e4m3_encode_int(r);
-}
-
-// Load 16 consecutive elements as FP32.
-__device__ __forceinline__ void load16(const float *src, float (&x)[16])
-{
-    const float4 *p = reinterpret_cast<const float4 *>(src);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float4 v = p[i];
-        x[4 * i + 0] = v.x; x[4 * i + 1] = v.y; x[4 * i + 2] = v.z; x[4 * i + 3] = v.w;
-    }
-}
 
 struct QuantParams {
     const void *X;
@@ -106,32 +91,6 @@ __device__ __forceinline__ void widen(const RawBlock<float> &r, float (&x)[16])
     }
 }
 
-// FP8 codes of 16 values (already multiplied by 1/S) as four dwords.
-template <bool kHW, bool kClamp> __device__ __forceinline__ void encode_fp8_block(const float (&r)[16], uint32_t (&c)[4])
-{
-    if constexpr (kHW) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            short2_t acc = {0, 0};
-            float a0 = r[4 * j], a1 = r[4 * j + 1], a2 = r[4 * j + 2], a3 = r[4 * j + 3];
-            if constexpr (kClamp) {   // the instruction returns NaN instead of saturating beyond 464
-                a0 = __builtin_amdgcn_fmed3f(a0, -448.0f, 448.0f);
-                a1 = __builtin_amdgcn_fmed3f(a1, -448.0f, 448.0f);
-                a2 = __builtin_amdgcn_fmed3f(a2, -448.0f, 448.0f);
-                a3 = __builtin_amdgcn_fmed3f(a3, -448.0f, 448.0f);
-            }
-            acc = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(acc, a0, a1, 1.0f, false);
-            acc = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(acc, a2, a3, 1.0f, true);
-            c[j] = (uint32_t)(uint16_t)acc[0] | ((uint32_t)(uint16_t)acc[1] << 16);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            c[j] = e4m3_encode_int(r[4 * j]) | (e4m3_encode_int(r[4 * j + 1]) << 8) |
-                   (e4m3_encode_int(r[4 * j + 2]) << 16) | (e4m3_encode_int(r[4 * j + 3]) << 24);
-    }
-}
-
 // grid.x = K-tiles, grid.y = groups of 4 * rt_per_wave row-tiles; 4 waves per
 // workgroup work on 4 adjacent row-tiles of the same K-tile at a time, so the
 // per-channel sensitivities stay in registers across the loop.  The input of
@@ -195,71 +154,20 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
             }
         }
 
-        // dynamic-max block scale
-        float amax = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(x[i]));
-        const float u = amax / S6;
-        uint32_t sc = enc_e4m3<kHW>(u);
-        if (p.sc_override != nullptr) sc = valid ? (uint32_t)p.sc_override[row * p.nb + kb] : 0u;
-        const float d = e4m3_decode_int(sc) * p.S;
-        const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
-
-        // Eq. 8 scoring: the block's FP8 codes, needed for every block
-        uint32_t c8[4] = {0u, 0u, 0u, 0u};
-        if constexpr (kDelta) {
-            // values beyond the FP8 range only occur when the caller's S is below amax / 448
-            const bool any_big = __ballot(amax * inv_S > 448.0f) != 0ull;
-            float r[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
-            if (any_big) encode_fp8_block<kHW, true>(r, c8);
-            else encode_fp8_block<kHW, false>(r, c8);
-        }
-
-        // NVFP4 codes, reconstruction, weighted squared error
-        uint32_t q[2] = {0u, 0u};
-        float t[16];
-        if constexpr (kHW) {
-            // each conversion fills one byte of the code word in place (the byte selector is an immediate)
-#define FGMP_ENC(W, B, I) q[W] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q[W], x[I] * inv_d, x[I + 1] * inv_d, 1.0f, B)
-            FGMP_ENC(0, 0, 0); FGMP_ENC(0, 1, 2); FGMP_ENC(0, 2, 4); FGMP_ENC(0, 3, 6);
-            FGMP_ENC(1, 0, 8); FGMP_ENC(1, 1, 10); FGMP_ENC(1, 2, 12); FGMP_ENC(1, 3, 14);
-#undef FGMP_ENC
-#define FGMP_ERR(W, B, I)                                                                          \
-    {                                                                                              \
-        const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);                \
-        float e0, e1;                                                                              \
-        if constexpr (kDelta) {                                                                    \
-            const float2_t v8 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c8[(I) / 4], 1.0f, ((I) % 4) >= 2); \
-            e0 = v[0] * d - v8[0] * p.S;                                                           \
-            e1 = v[1] * d - v8[1] * p.S;                                                           \
-        } else {                                                                                   \
-            e0 = x[I] - v[0] * d;                                                                  \
-            e1 = x[I + 1] - v[1] * d;                                                              \
-        }                                                                                          \
-        t[I] = (e0 * e0) * f[I];                                                                   \
-        t[I + 1] = (e1 * e1) * f[I + 1];                                                           \
-    }
-            FGMP_ERR(0, 0, 0) FGMP_ERR(0, 1, 2) FGMP_ERR(0, 2, 4) FGMP_ERR(0, 3, 6)
-            FGMP_ERR(1, 0, 8) FGMP_ERR(1, 1, 10) FGMP_ERR(1, 2, 12) FGMP_ERR(1, 3, 14)
-#undef FGMP_ERR
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t c = e2m1_encode_int(x[i] * inv_d);
-                q[i >> 3] |= c << (4 * (i & 7));
-                float e;
-                if constexpr (kDelta) e = e2m1_decode_int(c) * d - e4m3_decode_int((c8[i >> 2] >> (8 * (i & 3))) & 0xFFu) * p.S;
-                else e = x[i] - e2m1_decode_int(c) * d;
-                t[i] = (e * e) * f[i];
-            }
-        }
-#pragma unroll
-        for (int w = 16; w > 1; w >>= 1)
-#pragma unroll
-            for (int i = 0; i < w / 2; ++i) t[i] = t[2 * i] + t[2 * i + 1];
-        const float score = t[0];
+        // block scale (dynamic max, or chosen beforehand), NVFP4 codes, score; in the Eq. 8 mode also the
+        // FP8 codes of every block (values beyond the FP8 range only occur when the caller's S is below
+        // amax / 448: then the wave clamps before converting)
+        const float amax = block_amax(x);
+        bool clamp8 = false;
+        if constexpr (kDelta) clamp8 = __ballot(amax * inv_S > 448.0f) != 0ull;
+        int sc_given = -1;
+        if (p.sc_override != nullptr) sc_given = valid ? (int)p.sc_override[row * p.nb + kb] : 0;
+        BlockCodes bc;
+        quantize_block_math<kHW, kDelta>(x, f, amax, p.S, inv_S, S6, sc_given, clamp8, bc);
+        const uint32_t sc = bc.sc;
+        const uint32_t (&q)[2] = bc.q;
+        const uint32_t (&c8)[4] = bc.c8;
+        const float score = bc.score;
 
         const bool hi = valid && (score > p.T);
         const uint64_t ballot = __ballot(hi);
@@ -377,38 +285,12 @@ __global__ __launch_bounds__(256) void clip_scales_kernel(QuantParams p, uint8_t
     widen(raw, x);
     load16(p.fisher + (kPerElem ? row * p.ld_fisher : 0) + kb * kBlock, f);
 
+    const float amax = block_amax(x);
+    const float inv_S = 1.0f / p.S, S6 = 6.0f * p.S;
     auto error_with = [&](uint32_t sc) {
-        const float d = e4m3_decode_int(sc) * p.S;
-        const float inv_d = (sc != 0u) ? 1.0f / d : 0.0f;
-        float t[16];
-        if constexpr (kHW) {
-            uint32_t q[2] = {0u, 0u};
-#define FGMP_ENC(W, B, I) q[W] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q[W], x[I] * inv_d, x[I + 1] * inv_d, 1.0f, B)
-            FGMP_ENC(0, 0, 0); FGMP_ENC(0, 1, 2); FGMP_ENC(0, 2, 4); FGMP_ENC(0, 3, 6);
-            FGMP_ENC(1, 0, 8); FGMP_ENC(1, 1, 10); FGMP_ENC(1, 2, 12); FGMP_ENC(1, 3, 14);
-#undef FGMP_ENC
-#define FGMP_ERR(W, B, I)                                                              \
-    {                                                                                  \
-        const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);    \
-        const float e0 = x[I] - v[0] * d, e1 = x[I + 1] - v[1] * d;                    \
-        t[I] = (e0 * e0) * f[I];                                                       \
-        t[I + 1] = (e1 * e1) * f[I + 1];                                               \
-    }
-            FGMP_ERR(0, 0, 0) FGMP_ERR(0, 1, 2) FGMP_ERR(0, 2, 4) FGMP_ERR(0, 3, 6)
-            FGMP_ERR(1, 0, 8) FGMP_ERR(1, 1, 10) FGMP_ERR(1, 2, 12) FGMP_ERR(1, 3, 14)
-#undef FGMP_ERR
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float e = x[i] - e2m1_decode_int(e2m1_encode_int(x[i] * inv_d)) * d;
-                t[i] = (e * e) * f[i];
-            }
-        }
-#pragma unroll
-        for (int w = 16; w > 1; w >>= 1)
-#pragma unroll
-            for (int i = 0; i < w / 2; ++i) t[i] = t[2 * i] + t[2 * i + 1];
-        return t[0];
+        BlockCodes bc;
+        quantize_block_math<kHW, false>(x, f, amax, p.S, inv_S, S6, (int)sc, false, bc);
+        return bc.score;
     };
     uint32_t best = 0u;
     float best_err = error_with(0u);
