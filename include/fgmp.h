@@ -161,6 +161,26 @@ fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M
                                        int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The fused call with output-side quantization (Sec. 4.2: results are quantized before they are
+ * written to memory): Y = X^ * W^^T is not stored as FP32; each block of 16 consecutive output
+ * columns (= 16 consecutive input channels of the next layer) is scored (Eq. 6) with `fisher_n`,
+ * compared with `threshold_y` and stored as FP8 or NVFP4 in `packed_Y`, a packed M x N activation
+ * tensor (tensor scale `scale_y`) that the next layer's fgmp_gemm consumes.  The values that are
+ * quantized are exactly the FP32 numbers fgmp_quant_gemm_fused would have written.  For M > 32 this
+ * happens in the GEMM kernel's epilogue; smaller M stage the FP32 results in the workspace.
+ *   fisher_n   N FP32 sensitivities; N % 16 == 0
+ *   packed_Y   out, packed_Y_bytes >= fgmp_packed_bytes(M, N); scores_y nullable, M*N/16 FP32
+ *   workspace  >= fgmp_workspace_bytes_packed_out(M, N, K)
+ */
+size_t fgmp_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K);
+fgmp_status_t fgmp_quant_gemm_fused_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                               const float *fisher_k, float threshold, float scale_x,
+                                               const void *packed_W, int64_t N, const float *fisher_n,
+                                               float threshold_y, float scale_y, void *packed_Y,
+                                               size_t packed_Y_bytes, float *scores_y, void *workspace,
+                                               size_t workspace_bytes, void *stream);
+
+/*
  * Offline weight quantization with sensitivity-weighted clipping (Sec. 3.3, Eq. 11): the E4M3
  * scale of every block is the one, among all 127 non-negative E4M3 values, that minimizes
  * sum_i F_i (w_i - Q_s(w_i))^2 (the smallest such code if several tie) instead of the dynamic-max

@@ -309,14 +309,17 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
 // and the two-pass path go through the packed activations.
 fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
                          float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
-                         void *workspace, size_t workspace_bytes, hipStream_t st, int score_mode)
+                         void *workspace, size_t workspace_bytes, hipStream_t st, int score_mode,
+                         const PackOut *pack_out)
 {
-    if (!workspace || !packed_W || !Y) return FGMP_ERR_INVALID_ARG;
+    if (!workspace || !packed_W || (!Y && !pack_out)) return FGMP_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (K % kBlock != 0 || ldy < N) return FGMP_ERR_BAD_SHAPE;
     if (((uintptr_t)workspace | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
     if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
+    const bool in_kernel_prefill = !gemm_skinny_applies(M, N, K) && prefill_decodes_in_kernel() && kUseHwCvt;
+    if (pack_out != nullptr && !in_kernel_prefill) return FGMP_ERR_UNSUPPORTED;   // the caller falls back
     if (gemm_skinny_applies(M, N, K) && kUseHwCvt) {
         // decode shapes: FP16 values of X (rows beyond the last 8-row group stay unwritten: they only
         // feed output rows that are never stored), then the weight-streaming kernel
@@ -331,7 +334,7 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
         return gemm_skinny(reinterpret_cast<const PackedHeader *>(ws), make_layout(M, K), x16, ld16, packed_W,
                            make_layout(N, K), M, N, K, Y, ldy, sws, st);
     }
-    if (!gemm_skinny_applies(M, N, K) && prefill_decodes_in_kernel() && kUseHwCvt) {
+    if (in_kernel_prefill) {
         const GemmWorkspace w = gemm_ws_layout(M, N, K);
         const int64_t tiles_m = w.Mp / kBM, tiles_n = w.Np / kBN;
         if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
@@ -343,7 +346,7 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
         if (rc != FGMP_OK) return rc;
         const PackedLayout lb = make_layout(N, K);
         const PackedView B = make_view(const_cast<void *>(packed_W), lb);
-        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, hx, st);
+        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, hx, st, pack_out);
         return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
     }
     const size_t xbytes = (size_t)make_layout(M, K).total_bytes;
@@ -351,6 +354,49 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
                                              nullptr, false, st, nullptr, 0, nullptr, 0, score_mode);
     if (rc != FGMP_OK) return rc;
     return gemm_packed(ws, M, packed_W, N, K, Y, ldy, ws + xbytes, workspace_bytes - xbytes, st);
+}
+
+// Fused call whose results are quantized and packed instead of stored as FP32 (Sec. 4.2).  Prefill
+// shapes do it in the GEMM's epilogue; other shapes (and the two-pass path) write FP32 results to the
+// workspace and run the standalone quantizer over them -- the same arithmetic on the same values.
+size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K)
+{
+    return gemm_workspace_bytes(M, N, K) + (size_t)align_up((uint64_t)M * N * 4, 256);
+}
+
+fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                    const float *fisher_k, float threshold, float scale_x, const void *packed_W,
+                                    int64_t N, const float *fisher_n, float threshold_y, float scale_y,
+                                    void *packed_Y, size_t packed_Y_bytes, float *scores_y, void *workspace,
+                                    size_t workspace_bytes, hipStream_t st)
+{
+    if (!fisher_n || !packed_Y || !workspace) return FGMP_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (!(scale_y > 0.0f) || !(scale_y < INFINITY) || threshold_y != threshold_y) return FGMP_ERR_INVALID_ARG;
+    if (N % kBlock != 0 || K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    if (((uintptr_t)fisher_n | (uintptr_t)packed_Y | (uintptr_t)scores_y | (uintptr_t)workspace) % 16 != 0)
+        return FGMP_ERR_BAD_ALIGN;
+    if (M * (N / kBlock) >= (int64_t)1 << 32) return FGMP_ERR_UNSUPPORTED;
+    const PackedLayout ly = make_layout(M, N);
+    if (packed_Y_bytes < ly.total_bytes) return FGMP_ERR_BUFFER_TOO_SMALL;
+    if (workspace_bytes < gemm_workspace_bytes_packed_out(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
+    PackOut po;
+    po.out = make_view(packed_Y, ly);
+    po.layout = ly;
+    po.fisher = fisher_n;
+    po.T = threshold_y;
+    po.S = scale_y;
+    po.scores = scores_y;
+    const size_t base_bytes = gemm_workspace_bytes(M, N, K);
+    fgmp_status_t rc = quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, nullptr, N, workspace,
+                                  base_bytes, st, FGMP_SCORE_NVFP4_ERROR, &po);
+    if (rc != FGMP_ERR_UNSUPPORTED) return rc;
+    float *Yf = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up(base_bytes, 256));
+    rc = quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Yf, N, workspace, base_bytes, st,
+                    FGMP_SCORE_NVFP4_ERROR, nullptr);
+    if (rc != FGMP_OK) return rc;
+    return quantize_tensor(Yf, FGMP_F32, M, N, N, fisher_n, 0, threshold_y, scale_y, packed_Y, packed_Y_bytes,
+                           scores_y, /*compact=*/false, st);
 }
 
 }  // namespace fgmp

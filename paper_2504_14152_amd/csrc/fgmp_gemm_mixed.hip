@@ -15,6 +15,7 @@
 #include <type_traits>
 
 #include "fgmp_gemm_common.hpp"
+#include "fgmp_quant_block.hpp"
 
 namespace fgmp {
 
@@ -28,12 +29,15 @@ struct BRegs {
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-template <int kWM, int kWN>
+// kPackOut: instead of storing FP32 results, the epilogue scores and quantizes them block by block (16
+// consecutive output columns) and writes a packed tensor -- the placement of the quantization unit in
+// the paper (Sec. 4.2): results are quantized before they leave for memory.
+template <int kWM, int kWN, bool kPackOut>
 __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Float16 *__restrict__ A, int64_t ld,
                                                                        PackedView W, PackedLayout lw, int nk,
                                                                        float *__restrict__ Y, int64_t ldy, int64_t M,
                                                                        int64_t N, int64_t n_tm, int64_t n_tn,
-                                                                       const PackedHeader *ha)
+                                                                       const PackedHeader *ha, PackOut po)
 {
     constexpr int kWaves = kWM * kWN;
     static_assert(kWaves == 8, "the weight decode assigns two blocks per K-step to each of 512 threads");
@@ -223,25 +227,106 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
 
     const bool w_ok = W.hdr->magic == kMagic && W.hdr->rows == lw.rows && W.hdr->K == lw.K;
     const float ss = w_ok ? ha->tensor_scale * W.hdr->tensor_scale : 0.0f;
+    if constexpr (!kPackOut) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = tn * kBN + wn * (TN * 32) + j * 32 + (lane & 31);
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = tn * kBN + wn * (TN * 32) + j * 32 + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = tm * kBM + wm * (TM * 32) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = tm * kBM + wm * (TM * 32) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
+                }
+            }
+    } else {
+        // Each 32 x 32 accumulator tile is transposed through LDS (wave-private, the operand stages are
+        // free now) so that a lane owns one output block: (row = lane % 32, 16 columns = lane / 32).  The
+        // block goes through the quantizer's arithmetic; codes, scale bytes and FP8 upper halves are
+        // written by the lane, the mask words of the 64 packed tiles this workgroup covers are gathered
+        // in LDS.  Plane-H entries sit at the block's own slot (any unique index within the tile's
+        // 64-entry region is valid for a strided tensor).
+        constexpr int kTStride = 36;   // floats per transposed row: 16-byte aligned rows, staggered banks
+        __syncthreads();
+        float *tbuf = reinterpret_cast<float *>(&lds[0][0][0]) + wave * (32 * kTStride);
+        unsigned long long *m_lds = reinterpret_cast<unsigned long long *>(&lds[1][1][0]);
+        if (tid < 64) m_lds[tid] = 0ull;
+        __syncthreads();
+        const PackedLayout &ly = po.layout;
+        const float inv_Sy = 1.0f / po.S, S6y = 6.0f * po.S;
+        const int brow = lane & 31, bblk = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    tbuf[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kTStride + (lane & 31)] = acc[i][j][r] * ss;
+                float x[16], f[16];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float4 t4 = *reinterpret_cast<const float4 *>(&tbuf[brow * kTStride + 16 * bblk + 4 * v]);
+                    x[4 * v] = t4.x; x[4 * v + 1] = t4.y; x[4 * v + 2] = t4.z; x[4 * v + 3] = t4.w;
+                }
+                const int row_l = wm * (TM * 32) + i * 32 + brow;              // within the workgroup's 256 x 256
+                const int col_l = wn * (TN * 32) + j * 32 + 16 * bblk;
+                const int64_t row = tm * kBM + row_l, col0 = tn * kBN + col_l;
+                const bool valid = row < M && col0 < N;
+                if (valid) load16(po.fisher + col0, f);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    x[e] = valid ? x[e] : 0.0f;
+                    f[e] = valid ? f[e] : 0.0f;
+                }
+                const float amax = block_amax(x);
+                BlockCodes bc;
+                quantize_block_math<true, false>(x, f, amax, po.S, inv_Sy, S6y, -1, false, bc);
+                const bool hi = valid && bc.score > po.T;
+                if (po.scores != nullptr && valid) po.scores[row * ly.nb + (col0 >> 4)] = bc.score;
+                const int64_t rt = row >> 3, kt = col0 >> 7;
+                const int slot = (int)(row & 7) * kTileBlocks + (int)((col0 >> 4) & 7);
+                if (rt < ly.n_rt && kt < ly.n_kt) {
+                    const int64_t at = (rt * ly.n_kt + kt) * kTileSlots + slot;
+                    uint2 lword = make_uint2(bc.q[0], bc.q[1]);
+                    uint32_t sbyte = bc.sc;
+                    if (hi) {
+                        float rr[16];
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) rr[e] = x[e] * inv_Sy;
+                        uint32_t c[4];
+                        encode_fp8_block<true, true>(rr, c);
+                        lword = make_uint2(c[0], c[1]);
+                        po.out.H[at] = make_uint2(c[2], c[3]);
+                        sbyte = (uint32_t)slot;
+                        atomicOr(&m_lds[(row_l >> 3) * 2 + (col_l >> 7)], 1ull << slot);
+                    }
+                    po.out.L[at] = lword;
+                    po.out.S[at] = (uint8_t)sbyte;
+                }
+            }
+        __syncthreads();
+        if (tid < 64) {
+            const int64_t rt = tm * (kBM / kTileRows) + (tid >> 1), kt = tn * (kBN / kTileK) + (tid & 1);
+            if (rt < ly.n_rt && kt < ly.n_kt) {
+                const int64_t tile = rt * ly.n_kt + kt;
+                po.out.M[tile] = m_lds[tid];
+                po.out.T[tile] = (uint32_t)(tile * kTileSlots);
             }
         }
+        if (blockIdx.x == 0 && tid == 0) write_header(po.out.hdr, ly, po.S, 0u);
+    }
 }
 
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
-                       hipStream_t st)
+                       hipStream_t st, const PackOut *pack_out)
 {
-    hipLaunchKernelGGL((gemm_mixed_kernel<2, 4>), dim3((unsigned)(n_tm * n_tn)), dim3(512), 0, st, a16, ld, W, lw,
-                       (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha);
+    if (pack_out != nullptr)
+        hipLaunchKernelGGL((gemm_mixed_kernel<2, 4, true>), dim3((unsigned)(n_tm * n_tn)), dim3(512), 0, st, a16, ld, W,
+                           lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha, *pack_out);
+    else
+        hipLaunchKernelGGL((gemm_mixed_kernel<2, 4, false>), dim3((unsigned)(n_tm * n_tn)), dim3(512), 0, st, a16, ld, W,
+                           lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha, PackOut{});
 }
 
 }  // namespace fgmp

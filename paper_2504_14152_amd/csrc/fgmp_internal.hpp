@@ -29,11 +29,18 @@ fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
                           float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+struct PackOut;
 // quantize X and multiply in one call; `workspace` holds at least gemm_workspace_bytes(M, N, K)
 fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
                          float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
                          void *workspace, size_t workspace_bytes, hipStream_t st,
-                         int score_mode = FGMP_SCORE_NVFP4_ERROR);
+                         int score_mode = FGMP_SCORE_NVFP4_ERROR, const PackOut *pack_out = nullptr);
+size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K);
+fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                    const float *fisher_k, float threshold, float scale_x, const void *packed_W,
+                                    int64_t N, const float *fisher_n, float threshold_y, float scale_y,
+                                    void *packed_Y, size_t packed_Y_bytes, float *scores_y, void *workspace,
+                                    size_t workspace_bytes, hipStream_t st);
 // Decode shapes (few rows of X): weight-streaming kernel.  X is given as FP16 values (`x16`,
 // gemm_skinny_x16_rows(M) rows of ld16 halves; rows from M rounded up to 8 on are never used for a
 // stored output) plus the header of its packed form.
@@ -61,9 +68,17 @@ struct DecodeJob {
 DecodeJob make_decode_job(const PackedView &v, const PackedLayout &l, _Float16 *out, int64_t ld, int64_t n_rt_pad);
 fgmp_status_t launch_decode_f16(const DecodeJob &a, const DecodeJob *b, uint32_t *zero, int64_t zero_n,
                                 hipStream_t st);
+// Output-side quantization of the prefill GEMM: where the packed results go and how they are scored.
+struct PackOut {
+    PackedView out;        // packed M x N tensor ("strided"), N being the next layer's K
+    PackedLayout layout;
+    const float *fisher;   // N sensitivities (input channels of the next layer)
+    float T, S;            // threshold and tensor scale of the output tensor
+    float *scores;         // nullable, M * N / 16
+};
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
-                       hipStream_t st);
+                       hipStream_t st, const PackOut *pack_out = nullptr);
 fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);

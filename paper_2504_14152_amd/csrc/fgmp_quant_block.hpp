@@ -49,6 +49,24 @@ template <bool kHW, bool kClamp> __device__ __forceinline__ void encode_fp8_bloc
     }
 }
 
+// Header of a packed tensor (one thread of the kernel that writes the tensor calls this).
+__device__ __forceinline__ void write_header(PackedHeader *hdr, const PackedLayout &l, float S, uint32_t compact)
+{
+    hdr->magic = kMagic;
+    hdr->version = kVersion;
+    hdr->rows = l.rows;
+    hdr->K = l.K;
+    hdr->tensor_scale = S;
+    hdr->compact = compact;
+    hdr->off_L = l.off_L;
+    hdr->off_S = l.off_S;
+    hdr->off_M = l.off_M;
+    hdr->off_T = l.off_T;
+    hdr->off_H = l.off_H;
+    hdr->h_entries = (uint64_t)l.n_tiles * kTileSlots;   // a compact tensor's scan overwrites these two
+    hdr->bytes_used = l.total_bytes;
+}
+
 __device__ __forceinline__ float block_amax(const float (&x)[16])
 {
     float amax = 0.0f;

@@ -40,22 +40,6 @@ struct QuantParams {
 // what the prefill GEMM consumes; only the header goes to the packed buffer.
 enum { kModeStrided = 0, kModeCount = 1, kModeCompact = 2, kModeF16 = 3 };
 
-__device__ __forceinline__ void write_header(PackedHeader *hdr, const PackedLayout &l, float S, uint32_t compact)
-{
-    hdr->magic = kMagic;
-    hdr->version = kVersion;
-    hdr->rows = l.rows;
-    hdr->K = l.K;
-    hdr->tensor_scale = S;
-    hdr->compact = compact;
-    hdr->off_L = l.off_L;
-    hdr->off_S = l.off_S;
-    hdr->off_M = l.off_M;
-    hdr->off_T = l.off_T;
-    hdr->off_H = l.off_H;
-    hdr->h_entries = (uint64_t)l.n_tiles * kTileSlots;   // a compact tensor's scan overwrites these two
-    hdr->bytes_used = l.total_bytes;
-}
 
 // Raw (unconverted) 16 input elements of one block: 2 x 16 B of bf16 or 4 x 16 B of fp32.
 template <typename Tin> struct RawBlock;

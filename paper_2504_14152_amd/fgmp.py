@@ -59,6 +59,11 @@ def lib() -> ctypes.CDLL:
                                            vp, sz, vp]
     L.fgmp_quantize_weights_clip.restype = ctypes.c_int
     L.fgmp_quantize_weights_clip.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i64, f32, f32, vp, sz, vp, vp, sz, vp]
+    L.fgmp_workspace_bytes_packed_out.restype = sz
+    L.fgmp_workspace_bytes_packed_out.argtypes = [i64, i64, i64]
+    L.fgmp_quant_gemm_fused_packed_out.restype = ctypes.c_int
+    L.fgmp_quant_gemm_fused_packed_out.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, vp, f32, f32,
+                                                   vp, sz, vp, vp, sz, vp]
     L.fgmp_gemm.restype = ctypes.c_int
     L.fgmp_gemm.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp, sz, vp]
     L.fgmp_quant_gemm_fused.restype = ctypes.c_int
@@ -230,6 +235,28 @@ def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, 
                                             N, _ptr(Y), Y.stride(0), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "fgmp_quant_gemm_fused")
     return Y
+
+
+def quant_gemm_fused_packed_out(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, scale_x: float,
+                                pW: Packed, fisher_n: torch.Tensor, threshold_y: float, scale_y: float,
+                                want_scores: bool = False, out: Packed | None = None,
+                                workspace: torch.Tensor | None = None):
+    """Fused step whose results are quantized and packed (a packed M x N activation tensor)."""
+    _require_cuda(X, fisher_k, fisher_n)
+    M, K = X.shape
+    if K != pW.K:
+        raise FgmpError("K mismatch")
+    N = pW.rows
+    out = out or _alloc_packed(M, N, X.device)
+    scores = torch.empty((M, N // 16), dtype=torch.float32, device=X.device) if want_scores else None
+    if workspace is None:
+        workspace = torch.empty(int(lib().fgmp_workspace_bytes_packed_out(M, N, K)), dtype=torch.uint8, device=X.device)
+    rc = lib().fgmp_quant_gemm_fused_packed_out(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                                float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(fisher_n),
+                                                float(threshold_y), float(scale_y), _ptr(out.buf), out.buf.numel(),
+                                                _ptr(scores), _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "fgmp_quant_gemm_fused_packed_out")
+    return (out, scores) if want_scores else out
 
 
 def unpack_canonical(p: Packed):

@@ -95,3 +95,27 @@ def tiny_config(seed: int = 0) -> dict:
             "fisher_x": fisher_per_channel(K, seed, 3),
             "fisher_w": fisher_per_element(N, K, seed, 4),
             "scale_x": default_tensor_scale(x), "scale_w": default_tensor_scale(w)}
+
+
+def exact_sum_operand(rows: int, K: int, seed: int, tensor_id: int, fp8_block_fraction: float = 0.2) -> np.ndarray:
+    """A rows x K fp32 tensor made so that a product of two such tensors has no rounding at all for
+    K <= 128, whatever the summation order: every value is a multiple of 2**-4 of magnitude <= 12.
+    Each 16-element block is scaled by 2**j, j in {-1, 0, 1}; most blocks hold values from the grid
+    {0, .5, 1, 1.5, 2, 3, 4, 6} * 2**j with the value 6 * 2**j present, the others multiples of
+    2**j / 8 below 2 * 2**j.  (With a tensor scale of 1 the first kind is exactly representable as a
+    4-bit block with a power-of-two block scale, the second only as 8-bit floating point.)"""
+    rng = rng_for(seed, tensor_id)
+    nb = K // 16
+    grid4 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)
+    j = rng.integers(-1, 2, size=(rows, nb, 1)).astype(np.float32)
+    sign = rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=(rows, nb, 16))
+    a = grid4[rng.integers(0, 8, size=(rows, nb, 16))]
+    pos = rng.integers(0, 16, size=(rows, nb))
+    np.put_along_axis(a, pos[..., None], np.float32(6.0), axis=2)
+    b = rng.integers(0, 16, size=(rows, nb, 16)).astype(np.float32) / np.float32(8.0)
+    b[..., 0] = np.float32(1.875)          # not on the 4-bit grid for any block scale that also fits the rest
+    b[..., 1] = np.float32(0.125)
+    kind8 = rng.random(size=(rows, nb, 1)) < fp8_block_fraction
+    v = np.where(kind8, b, a) * sign * np.exp2(j).astype(np.float32)
+    return v.reshape(rows, K).astype(np.float32)
+

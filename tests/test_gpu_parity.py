@@ -360,6 +360,78 @@ def test_global_threshold_over_layers():
     assert fgmp.threshold_for_fraction_multi(dev_scores[:1], p) == fgmp.threshold_for_fraction(dev_scores[0], p)
 
 
+# ------------------------------------------------------------------ output-side quantization (Sec. 4.2)
+
+def _exact_product_case(M, K, N, seed):
+    """Operands whose stored form equals the input and whose product has no rounding in any summation
+    order, so that the FP32 results the epilogue quantizes are the oracle's results exactly."""
+    x = synth.exact_sum_operand(M, K, seed, 1)
+    w = synth.exact_sum_operand(N, K, seed, 2)
+    ones = np.ones(K, dtype=np.float32)
+    qx, qw = orc.quantize(x, ones, 0.0, 1.0), orc.quantize(w, ones, 0.0, 1.0)
+    ax, aw = orc.dequantize(qx["codes"], qx["scales"], qx["mask"]), orc.dequantize(qw["codes"], qw["scales"], qw["mask"])
+    assert np.array_equal(ax, x.astype(np.float64)) and np.array_equal(aw, w.astype(np.float64))
+    assert 0.1 < qx["mask"].mean() < 0.35 and 0.1 < qw["mask"].mean() < 0.35
+    y64, _ = orc.gemm(ax, 1.0, aw, 1.0)
+    y32 = y64.astype(np.float32)
+    assert np.array_equal(y32.astype(np.float64), y64)          # the results are fp32 numbers
+    assert np.abs(y64).max() * 256 < 2 ** 24                    # ... and so is every partial sum (multiples of 2^-8)
+    return x, w, ones, y32
+
+
+@pytest.mark.parametrize("M,K,N", [(136, 128, 272), (300, 64, 512), (257, 128, 48), (24, 128, 160)])
+def test_fused_packed_output_matches_oracle(M, K, N):
+    """GEMM whose results are scored, quantized and packed before they reach memory: codes, block
+    scales, decisions and scores equal the oracle's quantization of the oracle's product (M > 32: in
+    the GEMM epilogue; M = 24: staged through FP32)."""
+    _say(f"packed output M={M} K={K} N={N}")
+    x, w, ones, y32 = _exact_product_case(M, K, N, 31)
+    f_n = synth.fisher_per_channel(N, 31, 3)
+    s_y = float(np.float32(np.abs(y32).max()) / np.float32(448.0))
+    T_y = orc.threshold(orc.quantize(y32, f_n, np.inf, s_y)["scores"], 0.2)
+    want = orc.quantize(y32, f_n, T_y, s_y)
+    xd, wd, od = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV), torch.from_numpy(ones).to(DEV)
+    pW = fgmp.quantize_weights(wd, od, 0.0, 1.0)
+    Y = fgmp.quant_gemm_fused(xd, od, 0.0, 1.0, pW)
+    assert np.array_equal(Y.cpu().numpy(), y32)
+    pY, scores = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_n).to(DEV), T_y, s_y,
+                                                  want_scores=True)
+    _assert_quant_equal(pY, scores, want, "packed output")
+    info = fgmp.packed_info(pY)
+    assert info["rows"] == M and info["K"] == N and info["n_fp8_blocks"] == int(want["mask"].sum())
+    assert abs(info["tensor_scale"] - s_y) <= 1e-7 * s_y
+    # the packed result is an ordinary activation tensor: the next layer multiplies it
+    w2 = synth.weights(72, N, 31, 4)
+    w2d, w2ref = _to_dev_bf16(w2)
+    f2 = synth.fisher_per_channel(N, 31, 5)
+    s2 = float(synth.default_tensor_scale(w2ref))
+    pW2 = fgmp.quantize_weights(w2d, torch.from_numpy(f2).to(DEV), np.inf, s2)
+    Z = fgmp.gemm(pY, pW2)
+    q2 = orc.quantize(w2ref, f2, np.inf, s2)
+    zw, tol = orc.gemm(orc.dequantize(want["codes"], want["scales"], want["mask"]), s_y,
+                       orc.dequantize(q2["codes"], q2["scales"], q2["mask"]), s2)
+    assert np.all(np.abs(Z.cpu().numpy().astype(np.float64) - zw) <= tol)
+
+
+def test_packed_output_on_random_inputs_is_consistent():
+    """On ordinary inputs the FP32 results differ from the oracle's fp64 product in the last bits, so
+    codes cannot be compared one by one; the epilogue must still equal the standalone quantizer run on
+    the very FP32 results the plain fused call writes (same arithmetic, same values)."""
+    M, K, N = 200, 512, 272
+    c = _quantized_pair(M, K, N, 33, 0.1, per_elem_w=False)
+    f_n = torch.from_numpy(synth.fisher_per_channel(N, 33, 9)).to(DEV)
+    Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    s_y = float(Y.abs().max()) / 448.0
+    _, sc0 = fgmp.quantize_activations(Y, f_n, np.inf, s_y, want_scores=True)
+    T_y = fgmp.threshold_for_fraction(sc0, 0.2)
+    ref, sc_ref = fgmp.quantize_activations(Y, f_n, T_y, s_y, want_scores=True)
+    got, sc_got = fgmp.quant_gemm_fused_packed_out(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], f_n, T_y, s_y,
+                                                   want_scores=True)
+    assert torch.equal(sc_ref, sc_got)
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(ref), fgmp.unpack_canonical(got)))
+    assert fgmp.packed_info(got)["n_fp8_blocks"] == int(0.2 * M * N / 16 + 0.5)
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)
