@@ -19,11 +19,11 @@
 
 namespace fgmp {
 
-struct BRegs {
-    uint4 l;       // plane L: two adjacent blocks
-    uint32_t s;    // plane S: their two bytes
-    uint2 m;       // plane M word of the tile
-    uint32_t t;    // plane T entry of the tile
+template <int kBPT> struct BRegs {
+    uint4 l[kBPT / 2];   // plane L: kBPT adjacent blocks
+    uint32_t s;          // plane S: their bytes
+    uint2 m;             // plane M word of the tile
+    uint32_t t;          // plane T entry of the tile
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -40,7 +40,10 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
                                                                        const PackedHeader *ha, PackOut po)
 {
     constexpr int kWaves = kWM * kWN;
-    static_assert(kWaves == 8, "the weight decode assigns two blocks per K-step to each of 512 threads");
+    static_assert(kWaves == 8 || kWaves == 4, "the weight decode assigns 2 (512 threads) or 4 (256 threads) blocks per K-step to a thread");
+    constexpr int kBPT = 16 / kWaves;             // weight blocks per thread and K-step
+    constexpr int kBLoads = kBPT / 2 + 3 + kBPT;  // register loads per K-step: plane L, S, M, T, plane H
+    typedef BRegs<kBPT> BRegsT;
     constexpr int TM = kBM / (32 * kWM), TN = kBN / (32 * kWN);
     constexpr int kLoads = 32 / kWaves;
     __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];   // [stage][operand]
@@ -71,7 +74,7 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     // the loop).  Tile indices are clamped into the tensor, so every index read from it is valid. ----
     const __amdgpu_buffer_rsrc_t wbuf =
         __builtin_amdgcn_make_buffer_rsrc(W.hdr, 0, (int)(uint32_t)lw.total_bytes, 0x00020000);
-    const int br = tid >> 1, bp = tid & 1;
+    const int br = kBPT == 2 ? tid >> 1 : tid, bp = kBPT == 2 ? tid & 1 : 0;   // weight row; which pair of blocks
     const int64_t row_b = tn * kBN + br;
     // rows beyond the tensor read a valid tile; their products only reach output columns that are never stored
     const uint32_t rt_b = (uint32_t)((row_b >> 3) < lw.n_rt ? (row_b >> 3) : lw.n_rt - 1);
@@ -85,37 +88,42 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     const uint32_t vT = (uint32_t)lw.off_T + tile_b * 4u;
     const uint32_t off_H = (uint32_t)lw.off_H;
     const int m_shift = (r8 & 3) * 8 + 2 * bp;   // bit of the thread's first block of an even K-step in its mask dword
-    auto load_b = [&](int kt, BRegs &b) {
+    auto load_b = [&](int kt, BRegsT &b) {
         kt = kt < last_kt ? kt : last_kt;
         const uint32_t t2 = (uint32_t)__builtin_amdgcn_readfirstlane(kt) >> 1, odd = (uint32_t)__builtin_amdgcn_readfirstlane(kt) & 1u;   // K-tile, and which half of its 8 blocks
-        const u32x4_t l = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)vL, (int)(t2 * (kTileSlots * 8) + odd * 32), 0);
-        b.l = make_uint4(l[0], l[1], l[2], l[3]);
-        b.s = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(wbuf, (int)vS, (int)(t2 * kTileSlots + odd * 4), 0);
+#pragma unroll
+        for (int u = 0; u < kBPT / 2; ++u) {
+            const u32x4_t l = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)vL + 16 * u, (int)(t2 * (kTileSlots * 8) + odd * 32), 0);
+            b.l[u] = make_uint4(l[0], l[1], l[2], l[3]);
+        }
+        if constexpr (kBPT == 2) b.s = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(wbuf, (int)vS, (int)(t2 * kTileSlots + odd * 4), 0);
+        else b.s = __builtin_amdgcn_raw_buffer_load_b32(wbuf, (int)vS, (int)(t2 * kTileSlots + odd * 4), 0);
         const u32x2_t m = __builtin_amdgcn_raw_buffer_load_b64(wbuf, (int)vM, (int)(t2 * 8), 0);
         b.m = make_uint2(m[0], m[1]);
         b.t = __builtin_amdgcn_raw_buffer_load_b32(wbuf, (int)vT, (int)(t2 * 4), 0);
     };
-    // bits 0, 1 of the result: the thread's two blocks of K-step kt are FP8
-    auto hi_bits = [&](int kt, const BRegs &b) {
+    // bit j of the result: the thread's block j of K-step kt is FP8
+    auto hi_bits = [&](int kt, const BRegsT &b) {
         kt = kt < last_kt ? kt : last_kt;
         const uint32_t word = r8 < 4 ? b.m.x : b.m.y;
-        return (word >> (m_shift + (kt & 1) * 4)) & 3u;
+        return (word >> (m_shift + (kt & 1) * 4)) & ((1u << kBPT) - 1u);
     };
-    auto load_h = [&](int kt, const BRegs &b, uint2 (&h)[2]) {
+    auto load_h = [&](int kt, const BRegsT &b, uint2 (&h)[kBPT]) {
         const uint32_t bits = hi_bits(kt, b);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < kBPT; ++j) {
             const bool hi = (bits >> j) & 1u;
             const uint32_t idx = hi ? b.t + ((b.s >> (8 * j)) & 0xFFu) : 0u;
             const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(wbuf, (int)(off_H + idx * 8u), 0, 0);
             h[j] = make_uint2(v[0], v[1]);
         }
     };
-    auto decode_store = [&](int kt, const BRegs &b, const uint2 (&h)[2], int stage, int j) {
+    auto decode_store = [&](int kt, const BRegsT &b, const uint2 (&h)[kBPT], int stage, int j) {
         const uint32_t bits = hi_bits(kt, b);
         char *row = &lds[stage][1][br * kRowBytes];
         half2_t v[8];
-        decode_block(j ? make_uint2(b.l.z, b.l.w) : make_uint2(b.l.x, b.l.y), (b.s >> (8 * j)) & 0xFFu,
+        const uint4 &lq = b.l[j >> 1];
+        decode_block((j & 1) ? make_uint2(lq.z, lq.w) : make_uint2(lq.x, lq.y), (b.s >> (8 * j)) & 0xFFu,
                      (bits >> j) & 1u, h[j], v);
         const uint32_t *o = reinterpret_cast<const uint32_t *>(v);
         const int c = 2 * (2 * bp + j);   // the block's two 16-byte chunks within the 128-byte row
@@ -152,14 +160,14 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     constexpr int kReads = TM + TN, kMfma = TM * TN;
 
     // ---- prologue: K-step 0 decoded into stage 0; K-step 1 ready in registers; K-step 2 in flight ----
-    BRegs cur, nxt, far;
-    uint2 hcur[2], hnxt[2];
+    BRegsT cur, nxt, far;
+    uint2 hcur[kBPT], hnxt[kBPT];
     issue_a(0, 0);
     issue_a(nk > 1 ? 1 : 0, 1);
     load_b(0, cur);
     load_h(0, cur, hcur);
-    decode_store(0, cur, hcur, 0, 0);
-    decode_store(0, cur, hcur, 0, 1);
+#pragma unroll
+    for (int j = 0; j < kBPT; ++j) decode_store(0, cur, hcur, 0, j);
     load_b(1, cur);
     load_h(1, cur, hcur);
     load_b(2, nxt);
@@ -176,21 +184,21 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     // immediate; nk is even because the K extent is padded to whole 128-element tiles)
     auto k_step = [&](int kt, auto stage_c) {
         constexpr int st = decltype(stage_c)::value;
-        load_b(kt + 3, far);            // 4 register loads ...
-        load_h(kt + 2, nxt, hnxt);      // ... + 2: the only loads younger than the A loads at this iteration's barrier
+        load_b(kt + 3, far);            // plane L, S, M, T ...
+        load_h(kt + 2, nxt, hnxt);      // ... and plane H: the kBLoads loads younger than the A loads at this iteration's barrier
         read_frags(st, 1, fa[1], fb[1]);
         mfma_block(fa[0], fb[0]);
         // fragment reads first, then one weight load per MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
 #pragma unroll
-        for (int g = 0; g < 6; ++g) {
+        for (int g = 0; g < kBLoads; ++g) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kBLoads, 0);
         __builtin_amdgcn_sched_barrier(0);
-        decode_store(kt + 1, cur, hcur, st ^ 1, 0);
-        decode_store(kt + 1, cur, hcur, st ^ 1, 1);
+#pragma unroll
+        for (int j = 0; j < kBPT; ++j) decode_store(kt + 1, cur, hcur, st ^ 1, j);
         read_frags(st, 2, fa[0], fb[0]);
         mfma_block(fa[1], fb[1]);
         // fragment reads first, then the decode arithmetic spread between the MFMAs
@@ -198,16 +206,16 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
 #pragma unroll
         for (int g = 0; g < kMfma; ++g) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, kBPT == 2 ? 10 : 8, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x200, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x200, 2 * kBPT, 0);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(st, 3, fa[1], fb[1]);
         mfma_block(fa[0], fb[0]);
         order_phase<kReads, kMfma, 0>();
         // LDS traffic of this wave done (lgkmcnt 0) and its A loads landed: they are older than this
-        // iteration's six register loads, which may stay in flight (vmcnt 6)
-        __builtin_amdgcn_s_waitcnt(0x0076);
+        // iteration's kBLoads register loads, which may stay in flight (vmcnt kBLoads)
+        __builtin_amdgcn_s_waitcnt(0x0070 | kBLoads);
         __syncthreads();
         issue_a(kt + 2 < nk ? kt + 2 : nk - 1, st);
         read_frags(st ^ 1, 0, fa[0], fb[0]);
@@ -215,8 +223,8 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         order_phase<kReads, kMfma, kLoads / 2>();
         __builtin_amdgcn_s_waitcnt(0xC07F);
         cur = nxt;
-        hcur[0] = hnxt[0];
-        hcur[1] = hnxt[1];
+#pragma unroll
+        for (int j = 0; j < kBPT; ++j) hcur[j] = hnxt[j];
         nxt = far;
     };
     for (int kt = 0; kt < nk; kt += 2) {
@@ -321,12 +329,19 @@ void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, con
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
                        hipStream_t st, const PackOut *pack_out)
 {
+#ifndef FGMP_MIXED_WM
+#define FGMP_MIXED_WM 2
+#define FGMP_MIXED_WN 4
+#endif
+    constexpr int kThreads = FGMP_MIXED_WM * FGMP_MIXED_WN * 64;
     if (pack_out != nullptr)
-        hipLaunchKernelGGL((gemm_mixed_kernel<2, 4, true>), dim3((unsigned)(n_tm * n_tn)), dim3(512), 0, st, a16, ld, W,
-                           lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha, *pack_out);
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, true>), dim3((unsigned)(n_tm * n_tn)),
+                           dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
+                           *pack_out);
     else
-        hipLaunchKernelGGL((gemm_mixed_kernel<2, 4, false>), dim3((unsigned)(n_tm * n_tn)), dim3(512), 0, st, a16, ld, W,
-                           lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha, PackOut{});
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false>), dim3((unsigned)(n_tm * n_tn)),
+                           dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
+                           PackOut{});
 }
 
 }  // namespace fgmp
