@@ -41,6 +41,21 @@ def test_sizes_and_host_side_argument_checks():
     assert L.fgmp_gemm(None, 1, None, 1, 16, None, 1, None, 0, None) == -1
     assert L.fgmp_gemm(256, 1, 256, 1, 24, 256, 1, 256, 0, None) == -2
     assert L.fgmp_unpack_canonical(None, 1, 16, None, None, None, None) == -1
+    # the entry points added for the score of Eq. 8, clipping, packed output and the global threshold
+    assert L.fgmp_quantize_activations_ex(256, 0, 8, 128, 128, 256, 0.0, 1.0, 5, 256, 1 << 20, None, None) == -1
+    assert L.fgmp_quantize_weights_ex(None, 0, 8, 128, 128, None, 0, 0.0, 1.0, 1, None, 0, None, None) == -1
+    assert L.fgmp_quantize_weights_clip(256, 0, 8, 128, 128, 256, 0, 0.0, 1.0, 256, 1 << 20, None, None, 0, None) == -1
+    assert L.fgmp_quantize_weights_clip(256, 0, 8, 24, 24, 256, 0, 0.0, 1.0, 256, 1 << 20, None, 256, 64, None) == -2
+    assert L.fgmp_quantize_weights_clip(256, 0, 8, 128, 128, 256, 0, 0.0, 1.0, 256, 1 << 20, None, 256, 63, None) == -4
+    assert fgmp.lib().fgmp_workspace_bytes_packed_out(4096, 12288, 4096) >= fgmp.workspace_bytes(4096, 12288, 4096) + 4096 * 12288 * 4
+    assert fgmp.lib().fgmp_workspace_bytes_packed_out(64, 24, 128) == 0          # N must be a multiple of 16
+    assert L.fgmp_quant_gemm_fused_packed_out(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 24, 256, 0.0, 1.0, 256, 1 << 20,
+                                              None, 256, 1 << 20, None) == -2
+    assert L.fgmp_quant_gemm_fused_packed_out(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 32, 256, 0.0, 0.0, 256, 1 << 20,
+                                              None, 256, 1 << 20, None) == -1   # output scale must be positive
+    assert L.fgmp_quant_gemm_fused_packed_out(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 32, 256, 0.0, 1.0, 256, 16,
+                                              None, 256, 1 << 20, None) == -4   # packed output buffer too small
+    assert L.fgmp_threshold_for_fraction_multi(None, None, 1, ctypes.c_double(0.1), None, None) == -1
 
 
 def test_bench_refuses_more_than_one_gpu():
