@@ -58,7 +58,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(the path would shard over rows of X or rows of W without communication, see DESIGN.md)",
+              "(the path would shard over rows of X or rows of W without communication)",
               file=sys.stderr)
         return 2
 
