@@ -236,6 +236,13 @@ static bool prefill_decodes_in_kernel()
     return in_kernel;
 }
 
+// The MFMA kernel that decodes the weights itself addresses them with 32-bit buffer offsets; larger
+// weight tensors take the two-pass path.
+static bool mixed_kernel_applies(int64_t N, int64_t K)
+{
+    return prefill_decodes_in_kernel() && make_layout(N, K).total_bytes < 0xFFFFFF00ull;
+}
+
 // FP16 activations of a decode-shape call: gemm_skinny_x16_rows(M) rows
 static size_t skinny_x16_bytes(int64_t M, int64_t K)
 {
@@ -278,7 +285,7 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
         return gemm_skinny(A.hdr, la, x16, ld16, packed_W, lb, M, N, K, Y, ldy, sws, st);
     }
     const GemmWorkspace w = gemm_ws_layout(M, N, K);
-    if (prefill_decodes_in_kernel()) {
+    if (mixed_kernel_applies(N, K)) {
         // activations expanded to FP16 once (M x K is small); weights decoded inside the MFMA kernel
         _Float16 *x16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
         const int64_t tiles_m = w.Mp / kBM, tiles_n = w.Np / kBN;
@@ -318,7 +325,7 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
     if (((uintptr_t)workspace | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
     if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
-    const bool in_kernel_prefill = !gemm_skinny_applies(M, N, K) && prefill_decodes_in_kernel() && kUseHwCvt;
+    const bool in_kernel_prefill = !gemm_skinny_applies(M, N, K) && mixed_kernel_applies(N, K) && kUseHwCvt;
     if (pack_out != nullptr && !in_kernel_prefill) return FGMP_ERR_UNSUPPORTED;   // the caller falls back
     if (gemm_skinny_applies(M, N, K) && kUseHwCvt) {
         // decode shapes: FP16 values of X (rows beyond the last 8-row group stay unwritten: they only
@@ -361,7 +368,7 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
 // workspace and run the standalone quantizer over them -- the same arithmetic on the same values.
 size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K)
 {
-    return gemm_workspace_bytes(M, N, K) + (size_t)align_up((uint64_t)M * N * 4, 256);
+    return (size_t)align_up(gemm_workspace_bytes(M, N, K), 256) + (size_t)align_up((uint64_t)M * N * 4, 256);
 }
 
 fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,

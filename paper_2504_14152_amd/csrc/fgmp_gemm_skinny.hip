@@ -414,7 +414,7 @@ fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const 
     const SkinnyPlan p = skinny_plan(M, N, K);
     char *ws = static_cast<char *>(workspace);
     const size_t partial_bytes = p.off_counters - p.off_partial;
-    if (p.row_groups * p.ksplit > 0x7FFFFFFF || partial_bytes > 0x7FFFFFFFu || p.ksplit > 255)
+    if (p.row_groups * p.ksplit > 0x7FFFFFFF || partial_bytes > 0x7FFFFFFFu)
         return FGMP_ERR_UNSUPPORTED;
     if (!xh || !x16 || ld16 < lx.n_kt * kTileK || (uintptr_t)x16 % 16 != 0 || (ld16 * 2) % 16 != 0)
         return FGMP_ERR_BAD_SHAPE;
