@@ -21,8 +21,10 @@
  *     the outputs are unspecified; argument errors are detected on the host
  *     before anything is launched.
  *   - Inputs must be finite; NaN/Inf inputs give unspecified codes.
- *   - A packed tensor is an opaque, self-describing device buffer of
- *     fgmp_packed_bytes(rows, K) bytes (worst case: every block FP8).
+ *   - A packed tensor is an opaque, self-describing device buffer.  Writing one
+ *     needs fgmp_packed_bytes(rows, K) bytes (worst case: every block FP8); once
+ *     written, its first `bytes_used` bytes (fgmp_packed_info) are all that any
+ *     entry point reads.
  */
 #ifndef FGMP_H
 #define FGMP_H
