@@ -12,6 +12,16 @@
 // offset.  Loads run two K-steps ahead in registers (plane-H entries one step
 // ahead, since their address needs the mask and index bytes); every load is
 // unconditional, so outstanding loads can be counted at compile time.
+//
+// All memory loads of the main loop are written as assembly with hand-counted
+// waits.  The compiler files a global->LDS load under a different event class
+// than an ordinary load and, while both classes are pending, turns every wait
+// for a loaded register into vmcnt(0): a full memory round trip in every
+// K-step, because a load has always just been issued.  Loads complete in issue
+// order, so a wait only has to count the loads issued after the one it needs;
+// the register sets rotate by index (the loop body is instantiated for one
+// whole turn of the rotation), so a register that a load in flight will write
+// is never copied.
 #include <type_traits>
 
 #include "fgmp_gemm_common.hpp"
@@ -19,15 +29,55 @@
 
 namespace fgmp {
 
-template <int kBPT> struct BRegs {
-    uint4 l[kBPT / 2];   // plane L: kBPT adjacent blocks
-    uint32_t s;          // plane S: their bytes
-    uint2 m;             // plane M word of the tile
-    uint32_t t;          // plane T entry of the tile
-};
-
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+// Per thread and K-step: the plane-L words (needed when the step is decoded) and the small fields
+// (needed one step earlier, for the plane-H addresses).
+template <int kBPT> struct LRegs {
+    u32x4_t l[kBPT / 2];   // plane L: kBPT adjacent blocks
+};
+struct MetaRegs {
+    uint32_t s;            // plane S: the blocks' bytes
+    uint32_t m;            // the half of the tile's plane-M word that holds the thread's row
+    uint32_t t;            // plane T entry of the tile
+};
+
+// Buffer loads (range-checked: out-of-range lanes read zero) with a per-lane byte offset, a uniform
+// byte offset and an immediate one.  The destination holds the data only after a later
+// wait_loaded<>() that names it; until then the register must not be read.
+template <int kImm> __device__ __forceinline__ void load_b128(u32x4_t &d, __amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen offset:%4" : "=v"(d) : "v"(voff), "s"(r), "s"(soff), "n"(kImm));
+}
+__device__ __forceinline__ void load_b64(u32x2_t &d, __amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    asm volatile("buffer_load_dwordx2 %0, %1, %2, %3 offen" : "=v"(d) : "v"(voff), "s"(r), "s"(soff));
+}
+__device__ __forceinline__ void load_b32(uint32_t &d, __amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(d) : "v"(voff), "s"(r), "s"(soff));
+}
+__device__ __forceinline__ void load_b16(uint32_t &d, __amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    asm volatile("buffer_load_ushort %0, %1, %2, %3 offen" : "=v"(d) : "v"(voff), "s"(r), "s"(soff));
+}
+// Wait until at most kPending loads are outstanding; the named registers count as written here, so
+// no use of them can move above the wait.
+template <int kPending, int kBPT> __device__ __forceinline__ void wait_loaded(LRegs<kBPT> &b)
+{
+    if constexpr (kBPT == 2) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b.l[0]) : "n"(kPending));
+    else asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b.l[0]), "+v"(b.l[1]) : "n"(kPending));
+}
+template <int kPending> __device__ __forceinline__ void wait_loaded(MetaRegs &b)
+{
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b.s), "+v"(b.m), "+v"(b.t) : "n"(kPending));
+}
+template <int kPending, int kBPT> __device__ __forceinline__ void wait_loaded(u32x2_t (&h)[kBPT])
+{
+    if constexpr (kBPT == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(h[0]), "+v"(h[1]) : "n"(kPending));
+    else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]) : "n"(kPending));
+}
 
 // kPackOut: instead of storing FP32 results, the epilogue scores and quantizes them block by block (16
 // consecutive output columns) and writes a packed tensor -- the placement of the quantization unit in
@@ -43,7 +93,7 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     static_assert(kWaves == 8 || kWaves == 4, "the weight decode assigns 2 (512 threads) or 4 (256 threads) blocks per K-step to a thread");
     constexpr int kBPT = 16 / kWaves;             // weight blocks per thread and K-step
     constexpr int kBLoads = kBPT / 2 + 3 + kBPT;  // register loads per K-step: plane L, S, M, T, plane H
-    typedef BRegs<kBPT> BRegsT;
+    typedef LRegs<kBPT> LRegsT;
     constexpr int TM = kBM / (32 * kWM), TN = kBN / (32 * kWN);
     constexpr int kLoads = 32 / kWaves;
     __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];   // [stage][operand]
@@ -58,15 +108,17 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     // vector instructions on it. ----
     const int lr = lane >> 3, lc = (lane & 7) ^ (((wave * 8 + lr) >> 1) & 7);
     const char *a_tile = reinterpret_cast<const char *>(A + tm * kBM * ld);
-    uint32_t a_off[kLoads];
-#pragma unroll
-    for (int i = 0; i < kLoads; ++i) a_off[i] = (uint32_t)((kWaves * 8 * i + wave * 8 + lr) * ld * 2 + lc * 16);
+    const uint32_t a_off = (uint32_t)((wave * 8 + lr) * ld * 2 + lc * 16);
+    const int64_t a_step = (int64_t)kWaves * 8 * ld * 2;   // load i fetches rows 8 kWaves i + ...
     auto issue_a = [&](int kt, int stage) {
         const char *base = a_tile + (int64_t)kt * kRowBytes;
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(base + a_off[i]),
-                                             (lds_void_t *)&lds[stage][0][(kWaves * i + wave) * 1024], 16, 0, 0);
+        for (int i = 0; i < kLoads; ++i) {
+            // M0 carries the LDS address of the wave's 1 KB destination
+            const uint32_t dst = (uint32_t)(uintptr_t)(lds_void_t *)&lds[stage][0][(kWaves * i + wave) * 1024];
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(a_off), "s"(base + i * a_step)
+                         : "memory");
+        }
     };
 
     // ---- B: packed weights through registers.  Buffer loads: the per-thread offset is computed once,
@@ -84,51 +136,53 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     const uint32_t tile_b = rt_b * (uint32_t)lw.n_kt;                       // first tile of the thread's row-tile
     const uint32_t vL = (uint32_t)lw.off_L + (tile_b * kTileSlots + r8 * kTileBlocks + 2 * bp) * 8u;
     const uint32_t vS = (uint32_t)lw.off_S + tile_b * kTileSlots + r8 * kTileBlocks + 2 * bp;
-    const uint32_t vM = (uint32_t)lw.off_M + tile_b * 8u;
+    const uint32_t vM = (uint32_t)lw.off_M + tile_b * 8u + (r8 < 4 ? 0u : 4u);   // rows 0-3 of a tile: low half of its mask word
     const uint32_t vT = (uint32_t)lw.off_T + tile_b * 4u;
     const uint32_t off_H = (uint32_t)lw.off_H;
     const int m_shift = (r8 & 3) * 8 + 2 * bp;   // bit of the thread's first block of an even K-step in its mask dword
-    auto load_b = [&](int kt, BRegsT &b) {
+    auto load_l = [&](int kt, LRegsT &b) {
         kt = kt < last_kt ? kt : last_kt;
         const uint32_t t2 = (uint32_t)__builtin_amdgcn_readfirstlane(kt) >> 1, odd = (uint32_t)__builtin_amdgcn_readfirstlane(kt) & 1u;   // K-tile, and which half of its 8 blocks
-#pragma unroll
-        for (int u = 0; u < kBPT / 2; ++u) {
-            const u32x4_t l = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (int)vL + 16 * u, (int)(t2 * (kTileSlots * 8) + odd * 32), 0);
-            b.l[u] = make_uint4(l[0], l[1], l[2], l[3]);
-        }
-        if constexpr (kBPT == 2) b.s = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(wbuf, (int)vS, (int)(t2 * kTileSlots + odd * 4), 0);
-        else b.s = __builtin_amdgcn_raw_buffer_load_b32(wbuf, (int)vS, (int)(t2 * kTileSlots + odd * 4), 0);
-        const u32x2_t m = __builtin_amdgcn_raw_buffer_load_b64(wbuf, (int)vM, (int)(t2 * 8), 0);
-        b.m = make_uint2(m[0], m[1]);
-        b.t = __builtin_amdgcn_raw_buffer_load_b32(wbuf, (int)vT, (int)(t2 * 4), 0);
+        load_b128<0>(b.l[0], wbuf, vL, t2 * (kTileSlots * 8) + odd * 32);
+        if constexpr (kBPT == 4) load_b128<16>(b.l[kBPT / 2 - 1], wbuf, vL, t2 * (kTileSlots * 8) + odd * 32);
+    };
+    auto load_meta = [&](int kt, MetaRegs &b) {
+        kt = kt < last_kt ? kt : last_kt;
+        const uint32_t t2 = (uint32_t)__builtin_amdgcn_readfirstlane(kt) >> 1, odd = (uint32_t)__builtin_amdgcn_readfirstlane(kt) & 1u;
+        if constexpr (kBPT == 2) load_b16(b.s, wbuf, vS, t2 * kTileSlots + odd * 4);
+        else load_b32(b.s, wbuf, vS, t2 * kTileSlots + odd * 4);
+        load_b32(b.m, wbuf, vM, t2 * 8);
+        load_b32(b.t, wbuf, vT, t2 * 4);
     };
     // bit j of the result: the thread's block j of K-step kt is FP8
-    auto hi_bits = [&](int kt, const BRegsT &b) {
+    auto hi_bits = [&](int kt, const MetaRegs &b) {
         kt = kt < last_kt ? kt : last_kt;
-        const uint32_t word = r8 < 4 ? b.m.x : b.m.y;
-        return (word >> (m_shift + (kt & 1) * 4)) & ((1u << kBPT) - 1u);
+        return (b.m >> (m_shift + (kt & 1) * 4)) & ((1u << kBPT) - 1u);
     };
-    auto load_h = [&](int kt, const BRegsT &b, uint2 (&h)[kBPT]) {
+    auto load_h = [&](int kt, const MetaRegs &b, u32x2_t (&h)[kBPT]) {
         const uint32_t bits = hi_bits(kt, b);
 #pragma unroll
         for (int j = 0; j < kBPT; ++j) {
             const bool hi = (bits >> j) & 1u;
             const uint32_t idx = hi ? b.t + ((b.s >> (8 * j)) & 0xFFu) : 0u;
-            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(wbuf, (int)(off_H + idx * 8u), 0, 0);
-            h[j] = make_uint2(v[0], v[1]);
+            load_b64(h[j], wbuf, off_H + idx * 8u, 0u);
         }
     };
-    auto decode_store = [&](int kt, const BRegsT &b, const uint2 (&h)[kBPT], int stage, int j) {
+    // LDS destination of the thread's blocks: chunk c of the 128-byte row sits at position c ^ swz_b; the
+    // thread's chunks are 4 bp + d (kBPT == 2) or d (kBPT == 4), and XOR-ing d into the address of
+    // chunk d = 0 reaches them all, so one address register per stage is enough.
+    const uint32_t b_wr0 = (uint32_t)(kTileBytes + br * kRowBytes + ((((kBPT == 2 ? 4 * bp : 0)) ^ swz_b) << 4));
+    auto decode_store = [&](int kt, const LRegsT &bl, const MetaRegs &b, const u32x2_t (&h)[kBPT], int stage, int j) {
         const uint32_t bits = hi_bits(kt, b);
-        char *row = &lds[stage][1][br * kRowBytes];
+        char *base = &lds[0][0][0];
+        const uint32_t at = b_wr0 + (uint32_t)stage * (2 * kTileBytes);
         half2_t v[8];
-        const uint4 &lq = b.l[j >> 1];
-        decode_block((j & 1) ? make_uint2(lq.z, lq.w) : make_uint2(lq.x, lq.y), (b.s >> (8 * j)) & 0xFFu,
-                     (bits >> j) & 1u, h[j], v);
+        const u32x4_t &lq = bl.l[j >> 1];
+        decode_block((j & 1) ? make_uint2(lq[2], lq[3]) : make_uint2(lq[0], lq[1]), (b.s >> (8 * j)) & 0xFFu,
+                     (bits >> j) & 1u, make_uint2(h[j][0], h[j][1]), v);
         const uint32_t *o = reinterpret_cast<const uint32_t *>(v);
-        const int c = 2 * (2 * bp + j);   // the block's two 16-byte chunks within the 128-byte row
-        *reinterpret_cast<uint4 *>(row + ((c ^ swz_b) << 4)) = make_uint4(o[0], o[1], o[2], o[3]);
-        *reinterpret_cast<uint4 *>(row + (((c + 1) ^ swz_b) << 4)) = make_uint4(o[4], o[5], o[6], o[7]);
+        *reinterpret_cast<uint4 *>(base + (at ^ ((2 * j) << 4))) = make_uint4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<uint4 *>(base + (at ^ ((2 * j + 1) << 4))) = make_uint4(o[4], o[5], o[6], o[7]);
     };
 
     float16_t acc[TM][TN];
@@ -159,18 +213,34 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     };
     constexpr int kReads = TM + TN, kMfma = TM * TN;
 
-    // ---- prologue: K-step 0 decoded into stage 0; K-step 1 ready in registers; K-step 2 in flight ----
-    BRegsT cur, nxt, far;
-    uint2 hcur[kBPT], hnxt[kBPT];
+    // Register sets by K-step: plane-L words of step k live in lring[k % 2], the small fields in
+    // mring[k % 3], plane-H entries in hring[k % 2].  Loads per thread and K-step: kNM (planes S, M, T
+    // of step kt + 3), kNL (plane L of step kt + 2), kNH (plane H of step kt + 2), then -- after the
+    // barrier -- kLoads global->LDS loads of A.
+    constexpr int kNM = 3, kNL = kBPT / 2, kNH = kBPT;
+    static_assert(kNM + kNL + kNH == kBLoads, "load count");
+    LRegsT lring[2];
+    MetaRegs mring[3];
+    u32x2_t hring[2][kBPT];
+
+    // ---- prologue: K-step 0 decoded into stage 0; K-step 1 ready in registers; the small fields of
+    // K-step 2 in flight ----
     issue_a(0, 0);
     issue_a(nk > 1 ? 1 : 0, 1);
-    load_b(0, cur);
-    load_h(0, cur, hcur);
+    load_l(0, lring[0]);
+    load_meta(0, mring[0]);
+    wait_loaded<0>(lring[0]);
+    wait_loaded<0>(mring[0]);
+    load_h(0, mring[0], hring[0]);
+    wait_loaded<0>(hring[0]);
 #pragma unroll
-    for (int j = 0; j < kBPT; ++j) decode_store(0, cur, hcur, 0, j);
-    load_b(1, cur);
-    load_h(1, cur, hcur);
-    load_b(2, nxt);
+    for (int j = 0; j < kBPT; ++j) decode_store(0, lring[0], mring[0], hring[0], 0, j);
+    load_l(1, lring[1]);
+    load_meta(1, mring[1]);
+    wait_loaded<0>(lring[1]);
+    wait_loaded<0>(mring[1]);
+    load_h(1, mring[1], hring[1]);
+    load_meta(2, mring[2]);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     half8_t fa[2][TM], fb[2][TN];
@@ -180,36 +250,34 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     // Iteration kt multiplies K-step kt (stage kt & 1) and, before its barrier,
     // decodes K-step kt + 1 into the other stage; after the barrier that stage is
     // readable and the stage just consumed takes the A loads of K-step kt + 2.
-    // (the body is instantiated for both LDS stages, so every LDS address in it is a register plus an
-    // immediate; nk is even because the K extent is padded to whole 128-element tiles)
-    auto k_step = [&](int kt, auto stage_c) {
-        constexpr int st = decltype(stage_c)::value;
-        load_b(kt + 3, far);            // plane L, S, M, T ...
-        load_h(kt + 2, nxt, hnxt);      // ... and plane H: the kBLoads loads younger than the A loads at this iteration's barrier
+    // Loads in flight, oldest first, when iteration kt starts: planes S, M, T of step kt + 2 (kNM),
+    // plane L and plane H of step kt + 1 (kNL + kNH), A of step kt + 1 (kLoads).
+    // (the body is instantiated for kt % 6 = 0..5, so every LDS address in it is a register plus an
+    // immediate and every register set is named statically)
+    auto k_step = [&](int kt, auto phase_c) {
+        constexpr int r = decltype(phase_c)::value, st = r & 1;
+        LRegsT &lcur = lring[(r + 1) % 2], &lnxt = lring[r % 2];
+        MetaRegs &mcur = mring[(r + 1) % 3], &mnxt = mring[(r + 2) % 3], &mfar = mring[r % 3];
+        u32x2_t(&hcur)[kBPT] = hring[(r + 1) % 2], (&hnxt)[kBPT] = hring[r % 2];
         read_frags(st, 1, fa[1], fb[1]);
+        load_meta(kt + 3, mfar);
+        // everything issued one iteration ago has landed: the small fields of step kt + 2, plane L and
+        // plane H of step kt + 1
+        wait_loaded<kLoads + kNM>(mnxt);
+        wait_loaded<kLoads + kNM>(lcur);
+        wait_loaded<kLoads + kNM>(hcur);
         mfma_block(fa[0], fb[0]);
-        // fragment reads first, then one weight load per MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
-#pragma unroll
-        for (int g = 0; g < kBLoads; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kBLoads, 0);
         __builtin_amdgcn_sched_barrier(0);
+        // The decode is a stretch of vector arithmetic with no MFMA in it (its FP8 / NVFP4 branches keep
+        // the scheduler from interleaving any); the other wave of the SIMD keeps the matrix pipe busy.
 #pragma unroll
-        for (int j = 0; j < kBPT; ++j) decode_store(kt + 1, cur, hcur, st ^ 1, j);
+        for (int j = 0; j < kBPT; ++j) decode_store(kt + 1, lcur, mcur, hcur, st ^ 1, j);
+        // the registers of the step just decoded take the loads of step kt + 2
+        load_l(kt + 2, lnxt);
+        load_h(kt + 2, mnxt, hnxt);
         read_frags(st, 2, fa[0], fb[0]);
         mfma_block(fa[1], fb[1]);
-        // fragment reads first, then the decode arithmetic spread between the MFMAs
-        __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
-#pragma unroll
-        for (int g = 0; g < kMfma; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, kBPT == 2 ? 10 : 8, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x200, 2 * kBPT, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        order_phase<kReads, kMfma, 0>();
         read_frags(st, 3, fa[1], fb[1]);
         mfma_block(fa[0], fb[0]);
         order_phase<kReads, kMfma, 0>();
@@ -220,17 +288,37 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         issue_a(kt + 2 < nk ? kt + 2 : nk - 1, st);
         read_frags(st ^ 1, 0, fa[0], fb[0]);
         mfma_block(fa[1], fb[1]);
-        order_phase<kReads, kMfma, kLoads / 2>();
+        order_phase<kReads, kMfma, 0>();
         __builtin_amdgcn_s_waitcnt(0xC07F);
-        cur = nxt;
-#pragma unroll
-        for (int j = 0; j < kBPT; ++j) hcur[j] = hnxt[j];
-        nxt = far;
     };
-    for (int kt = 0; kt < nk; kt += 2) {
+    // whole turns of the rotation, then the 0, 2 or 4 K-steps left (nk is even: the K extent is padded
+    // to whole 128-element tiles)
+    int kt = 0;
+    for (; kt + 6 <= nk; kt += 6) {
         k_step(kt, std::integral_constant<int, 0>{});
         k_step(kt + 1, std::integral_constant<int, 1>{});
+        k_step(kt + 2, std::integral_constant<int, 2>{});
+        k_step(kt + 3, std::integral_constant<int, 3>{});
+        k_step(kt + 4, std::integral_constant<int, 4>{});
+        k_step(kt + 5, std::integral_constant<int, 5>{});
     }
+    if (kt < nk) {
+        k_step(kt, std::integral_constant<int, 0>{});
+        k_step(kt + 1, std::integral_constant<int, 1>{});
+        if (kt + 2 < nk) {
+            k_step(kt + 2, std::integral_constant<int, 2>{});
+            k_step(kt + 3, std::integral_constant<int, 3>{});
+        }
+    }
+    // The last iterations load past the K range (clamped, unused): every register a load may still
+    // write stays reserved until all loads have landed.
+    wait_loaded<0>(lring[0]);
+    wait_loaded<0>(lring[1]);
+    wait_loaded<0>(mring[0]);
+    wait_loaded<0>(mring[1]);
+    wait_loaded<0>(mring[2]);
+    wait_loaded<0>(hring[0]);
+    wait_loaded<0>(hring[1]);
     __builtin_amdgcn_s_waitcnt(0);
 
     const bool w_ok = W.hdr->magic == kMagic && W.hdr->rows == lw.rows && W.hdr->K == lw.K;
@@ -244,7 +332,11 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int64_t row = tm * kBM + wm * (TM * 32) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+#ifdef FGMP_ABL_NOSTORE
+                    if (row < M && col < N && acc[i][j][r] == 12345.678f) Y[row * ldy + col] = acc[i][j][r] * ss;
+#else
                     if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
+#endif
                 }
             }
     } else {
