@@ -126,7 +126,11 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     // the loop).  Tile indices are clamped into the tensor, so every index read from it is valid. ----
     const __amdgpu_buffer_rsrc_t wbuf =
         __builtin_amdgcn_make_buffer_rsrc(W.hdr, 0, (int)(uint32_t)lw.total_bytes, 0x00020000);
-    const int br = kBPT == 2 ? tid >> 1 : tid, bp = kBPT == 2 ? tid & 1 : 0;   // weight row; which pair of blocks
+    // weight row and which pair of its blocks.  Lane pairs share a row; rows are dealt so that eight
+    // consecutive lanes -- what the LDS takes from a 16-byte write per clock -- hold rows r, r+2, r+4, r+6:
+    // with the swizzle below their chunks then fall into eight different 16-byte bank groups (dealing the
+    // rows in order gave 20% bank-conflict cycles on these writes).
+    const int br = kBPT == 2 ? (tid >> 4) * 8 + 2 * ((tid >> 1) & 3) + ((tid >> 3) & 1) : tid, bp = kBPT == 2 ? tid & 1 : 0;
     const int64_t row_b = tn * kBN + br;
     // rows beyond the tensor read a valid tile; their products only reach output columns that are never stored
     const uint32_t rt_b = (uint32_t)((row_b >> 3) < lw.n_rt ? (row_b >> 3) : lw.n_rt - 1);
