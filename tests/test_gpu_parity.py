@@ -516,7 +516,7 @@ def test_gemm_tiny_full(p):
 
 
 @pytest.mark.parametrize("M,K,N,p", [(256, 4096, 512, 0.1), (200, 304, 136, 0.3), (1, 128, 8, 0.1),
-                                     (130, 1024, 260, 0.5)])
+                                     (130, 1024, 260, 0.5), (72, 768, 264, 0.2), (40, 1280, 40, 0.1)])
 def test_gemm_mid_full(M, K, N, p):
     _say(f"gemm mid M={M} K={K} N={N} p={p}")
     c = _quantized_pair(M, K, N, 7, p)
