@@ -369,8 +369,11 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     p.waves = p.mt == 1 ? 4 : 8;
     const int64_t rows_per_wg = 16 * p.waves;
     p.row_groups = (N + rows_per_wg - 1) / rows_per_wg;
-    // about three workgroups per CU, at most 8 K-tiles each
-    const int64_t target_wgs = p.mt == 1 ? 768 : 384;
+    // At least one workgroup per CU, each with as many K-tiles as its LDS holds: further splitting of K
+    // only shortens a workgroup's stream below its start-up latency and lengthens the sum over K ranges
+    // (Llama-2-7B O projection, N = K = 4096, M = 8: 13.2 us with 256 workgroups of 8 K-tiles, 17.0 us
+    // with 704 of 3); more workgroups than are resident at once pay the start-up twice.
+    const int64_t target_wgs = p.mt == 1 ? 256 : 128;
     int64_t want = (target_wgs + p.row_groups - 1) / p.row_groups;
     const int max_cols = skinny_max_cols(p.mt);
     const int64_t need = (lw.n_kt + max_cols - 1) / max_cols;
