@@ -587,10 +587,12 @@ def test_gemm_fc2_shape_sampled():
 
 @pytest.mark.parametrize("M,K,N,p", [(1, 4096, 4096, 0.1), (8, 4096, 4096, 0.1), (32, 4096, 4096, 0.1),
                                      (17, 11008, 4096, 0.1), (5, 304, 100, 0.3), (32, 1024, 72, 1.0),
-                                     (16, 2048, 264, 0.5), (3, 4096, 12288, 0.0)])
+                                     (16, 2048, 264, 0.5), (3, 4096, 12288, 0.0), (5, 4096, 14000, 0.1),
+                                     (9, 11008, 8200, 0.2)])
 def test_gemm_decode_shapes(M, K, N, p):
     """Weight-streaming path (M <= 32): K ranges combined in K order, ragged N and
-    K, and FP8 fractions beyond the speculative plane-H window."""
+    K, FP8 fractions beyond the speculative plane-H window, and weight tensors with
+    so many rows that workgroups take 128 instead of 64 of them."""
     _say(f"gemm decode M={M} K={K} N={N} p={p}")
     c = _quantized_pair(M, K, N, 11, p, per_elem_w=False)
     Y = fgmp.gemm(c["pX"], c["pW"])
