@@ -38,7 +38,7 @@ PREHEAT_S = 0.08                # untimed load before the warm-up steps (clock r
 # HBM-side bytes of one gemm_mixed_kernel launch on this workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (KiB per dispatch; FETCH_SIZE reads half of a known-size copy's bytes and is scaled by 2,
 # WRITE_SIZE reads it exactly): see profiles/gemm_mixed_kernel_qkv_prefill_traffic.txt
-GEMM_KERNEL_HBM_BYTES = int((2 * 2.276e5 + 1.966e5) * 1024)
+GEMM_KERNEL_HBM_BYTES = int((2 * 1.603e5 + 1.966e5) * 1024)
 
 
 def bytes_per_block(p: float) -> float:
