@@ -6,12 +6,14 @@
 // expanding W to FP16 in memory first, the kernel pulls 0.6 instead of 2 bytes
 // per weight through the cache hierarchy and the expansion pass disappears.
 //
-// Thread t of the 512 owns weight row t / 2 of the 256-row tile and, per
-// 64-wide K-step, the two blocks 2 (t % 2), 2 (t % 2) + 1: one 16-byte load
-// from plane L, two scale-or-index bytes, the tile's mask word and plane-H
-// offset.  Loads run two K-steps ahead in registers (plane-H entries one step
-// ahead, since their address needs the mask and index bytes); every load is
-// unconditional, so outstanding loads can be counted at compile time.
+// Each pair of the 512 threads owns one weight row of the 256-row tile; a
+// thread handles, per 64-wide K-step, the two blocks 2 (t % 2), 2 (t % 2) + 1:
+// one 16-byte load from plane L, two scale-or-index bytes, the row's half of
+// the tile's mask word and the tile's plane-H offset.  The small fields are
+// loaded three K-steps before their blocks are multiplied, plane L and the
+// plane-H entries (whose addresses need the small fields) two, and the decode
+// into LDS runs one step ahead; every load is unconditional, so outstanding
+// loads can be counted at compile time.
 //
 // All memory loads of the main loop are written as assembly with hand-counted
 // waits.  The compiler files a global->LDS load under a different event class
