@@ -233,6 +233,26 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     const uint32_t *t_rel = &t_lds[wave][my_sel * 8];
     const uint2 *h_win = &h_lds[wave][my_sel][0];
 
+    // Everything a tile's decode looks up -- mask byte, scale-or-index bytes, the tile's offset into the
+    // plane-H window and, through those, the upper halves of its FP8 blocks -- is fetched from LDS for
+    // all K-tiles of the range at once, before the loop: two rounds of independent reads instead of a
+    // chain of dependent LDS round trips inside every tile.  (Tiles past the range read other bytes of
+    // the wave's LDS, or zeros beyond it; they are never consumed.)
+    uint32_t mb[kSkMaxCols], sv[kSkMaxCols], tr[kSkMaxCols];
+#pragma unroll
+    for (int c = 0; c < kSkMaxCols; ++c) {
+        mb[c] = m_byte[c * 8];
+        sv[c] = s_pair[c * (kTileSlots / 2)];
+        tr[c] = t_rel[c];
+    }
+    uint2 up_a[kSkMaxCols], up_b[kSkMaxCols];
+#pragma unroll
+    for (int c = 0; c < kSkMaxCols; ++c) {
+        const uint32_t e0 = tr[c] + (sv[c] & 0xFFu), e1 = tr[c] + (sv[c] >> 8);
+        up_a[c] = h_win[e0 < (uint32_t)kSkHWin ? e0 : 0u];
+        up_b[c] = h_win[e1 < (uint32_t)kSkHWin ? e1 : 0u];
+    }
+
     // The activation loads were issued before the per-tile words that the code above has waited for,
     // and loads complete in order: they have landed.
     __syncthreads();
@@ -242,18 +262,14 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     for (int i = 0; i < MT; ++i) acc[i] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
     const _Float16 *xrow = &xs[nl][32 * g];
-    auto consume = [&](int c, const SkinnyStage &st) {
-        const uint32_t mbits = (uint32_t)m_byte[c * 8] >> (2 * g);   // bits 0, 1: blocks 2g, 2g+1 are FP8
-        const uint32_t sv = s_pair[c * (kTileSlots / 2)];
-        const uint32_t s0 = sv & 0xFFu, s1 = sv >> 8;
+    auto consume = [&](int c, const SkinnyStage &st, uint32_t mbyte, uint32_t svc, uint32_t trel, uint2 up0, uint2 up1) {
+        const uint32_t mbits = mbyte >> (2 * g);   // bits 0, 1: blocks 2g, 2g+1 are FP8
+        const uint32_t s0 = svc & 0xFFu, s1 = svc >> 8;
         const bool hi0 = mbits & 1u, hi1 = mbits & 2u;
-        // upper halves of FP8 blocks: entry (tile's offset in the window + index byte) of the staged window
-        const uint32_t trel = t_rel[c];
-        const uint32_t e0 = trel + s0, e1 = trel + s1;
-        uint2 up0 = h_win[e0 < (uint32_t)kSkHWin ? e0 : 0u], up1 = h_win[e1 < (uint32_t)kSkHWin ? e1 : 0u];
         // K ranges with more FP8 blocks than the window holds: fetch directly.  Rare; the wait sits
         // inside the branch so that the common path keeps counting only its own prefetches.
         if (any_far) {
+            const uint32_t e0 = trel + s0, e1 = trel + s1;   // entry = tile's offset in the window + index byte
             const uint32_t my_start = my_sel ? startB : startA;
             if (hi0 && e0 >= (uint32_t)kSkHWin) up0 = ld64(hbuf, a.off_H + (my_start + e0) * 8u);
             if (hi1 && e1 >= (uint32_t)kSkHWin) up1 = ld64(hbuf, a.off_H + (my_start + e1) * 8u);
@@ -273,19 +289,16 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
             }
         }
     };
-    // The ring is indexed statically (the loop body covers one turn of it): a stage's registers are
-    // the targets of loads in flight and must not be copied.  Tiles past the K range read other bytes
-    // of the buffer (or zeros) that are never consumed.
-#pragma unroll 1
-    for (int c0r = 0; c0r < ncols; c0r += kSkPrefetch) {
+    // One pass over the range's tiles, instantiated per tile: the plane-L ring and the looked-up words
+    // are indexed statically (a ring stage's registers are the targets of loads in flight and must not
+    // be copied).  Tiles past the K range load other bytes of the buffer (or zeros) that are never
+    // consumed.
 #pragma unroll
-        for (int p = 0; p < kSkPrefetch; ++p) {
-            const int c = c0r + p;
-            if (c < ncols) consume(c, ring[p]);
-            issue_l(c + kSkPrefetch, ring[p]);
-        }
+    for (int c = 0; c < kSkMaxCols; ++c) {
+        if (c < ncols) consume(c, ring[c % kSkPrefetch], mb[c], sv[c], tr[c], up_a[c], up_b[c]);
+        if (c + kSkPrefetch < kSkMaxCols) issue_l(c + kSkPrefetch, ring[c % kSkPrefetch]);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the prefetches issued past the K range
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the plane-L loads of tiles past the K range
 
     float *const Y = a.Y;
     const int64_t ldy = a.ldy, M = a.M, N = a.N;
