@@ -158,15 +158,22 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
 
     // ---- activations: 16 MT rows x (ncols * 128) halves, straight into LDS; one wave-load fills
     // 1 KB = half a row of 8 K-tiles.  Chunks past the K range re-read the row's first chunk (never used).
+    // Written as assembly: while a global->LDS load that the compiler knows of is pending, it turns
+    // every wait for an ordinary load into vmcnt(0), and the start-up below lives on exact waits (the
+    // plane-H window can be requested as soon as the plane-T words are here, with the plane-L ring
+    // still in flight).  Loads complete in issue order and these are the first, so every later wait
+    // for a loaded register also covers them.
 #pragma unroll
     for (int u = 0; u < 32 * MT / kWaves; ++u) {
         const int id = wave + kWaves * u, r = id >> 1, h = id & 1;
         const int chunk = h * 64 + lane;
         const int src_chunk = chunk < ncols * (kTileK / 8) ? chunk : 0;
         // (a row of fewer than 8 K-tiles ends inside the second wave-load: the lanes beyond it stay out)
-        if (chunk < kSkMaxCols * (kTileK / 8))
-            __builtin_amdgcn_global_load_lds((global_void_t *)(xg + r * x_row_bytes + src_chunk * 16),
-                                             (lds_void_t *)&xs[r][h * 512], 16, 0, 0);
+        if (chunk < kSkMaxCols * (kTileK / 8)) {
+            const uint32_t dst = (uint32_t)(uintptr_t)(lds_void_t *)&xs[r][h * 512];   // M0: the wave's LDS destination
+            const uint32_t voff = (uint32_t)(r * x_row_bytes + src_chunk * 16);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(xg) : "memory");
+        }
     }
     __builtin_amdgcn_sched_barrier(0);   // keep these loads ahead of all others (see the barrier below)
 
@@ -184,9 +191,13 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
         // the K-tile displacement is uniform: it travels in the scalar offset, not through the vector ALU
         st.l = ld128(wbuf, voff_L, (uint32_t)(kTileSlots * 8) * c);
     };
+    // The first half of the plane-L ring goes out now; the second half follows the plane-H window loads
+    // below, which depend on the plane-T words: every workgroup of the launch starts at the same time, and
+    // behind the whole ring (4 KB per wave, 12 MB over the chip) those loads would wait a microsecond longer.
     SkinnyStage ring[kSkPrefetch];
-#pragma unroll
-    for (int p = 0; p < kSkPrefetch; ++p) issue_l(p, ring[p]);
+    static_assert(kSkPrefetch == 4, "two stages before, two after the plane-H window loads");
+    issue_l(0, ring[0]);
+    issue_l(1, ring[1]);
 
     // header fields: magic at byte 0, rows at 8, K at 16, tensor_scale at 24, h_entries at 72, bytes_used at 80
     auto hdr_ok = [](const uint4 &h0, const uint4 &h1, int64_t rows, int64_t K) {
@@ -209,25 +220,34 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     const uint32_t needA = endA - startA, needB = endB - startB;       // entries (garbage rows: any value)
     // any FP8 block of this wave beyond the staged window?  (then those blocks fetch their entry directly)
     const bool any_far = needA > (uint32_t)kSkHWin || needB > (uint32_t)kSkHWin;
-    {
-        // 128 entries (1 KB) per wave-load and row-tile; as many loads as the fuller row-tile needs
-        const uint32_t need = needA > needB ? needA : needB;
-        const uint32_t my_start = (lane >> 5) ? startB : startA;   // lanes 0-31: row-tile A, 32-63: row-tile B
-#pragma unroll
-        for (int u = 0; u < kSkHWin / 64; ++u) {
-            if ((uint32_t)(64 * u) < need) {
-                const uint32_t e = 64u * u + 2u * (lane & 31);
-                const uint4 hv = ld128(hbuf, a.off_H + (my_start + e) * 8u);
-                *reinterpret_cast<uint4 *>(&h_lds[wave][lane >> 5][e]) = hv;
-            }
-        }
-    }
     if (lane < 16) {
         m_lds[wave][lane] = mvec;
         t_lds[wave][lane] = tvec - (w_sel ? startB : startA);
     }
     *reinterpret_cast<uint4 *>(&s_lds[wave][lane >> 5][(lane & 31) * 16]) = svec;
     // (written and read by the same wave, LDS operations of a wave execute in order: no barrier needed)
+    {
+        // 128 entries (1 KB) per wave-load and row-tile; as many loads as the fuller row-tile needs
+        const uint32_t need = needA > needB ? needA : needB;
+        const uint32_t my_start = (lane >> 5) ? startB : startA;   // lanes 0-31: row-tile A, 32-63: row-tile B
+        // the first 64 entries per row-tile unconditionally (nearly always all that is needed; a load
+        // the compiler knows to be issued gets an exact wait, which leaves the two plane-L loads
+        // behind it in flight), the rest only if the range holds more
+        const uint32_t e = 2u * (lane & 31);
+        const uint4 hv0 = ld128(hbuf, a.off_H + (my_start + e) * 8u);
+        issue_l(2, ring[2]);
+        issue_l(3, ring[3]);
+        *reinterpret_cast<uint4 *>(&h_lds[wave][lane >> 5][e]) = hv0;
+        // (load and store in one branch: a load left pending at the end of a branch would make every
+        // later wait a full one)
+#pragma unroll
+        for (int u = 1; u < kSkHWin / 64; ++u) {
+            if ((uint32_t)(64 * u) < need) {
+                const uint4 hv = ld128(hbuf, a.off_H + (my_start + 64u * u + e) * 8u);
+                *reinterpret_cast<uint4 *>(&h_lds[wave][lane >> 5][64u * u + e]) = hv;
+            }
+        }
+    }
     const uint8_t *m_byte = reinterpret_cast<const uint8_t *>(&m_lds[wave][my_sel * 8]) + (nl & 7);
     const uint16_t *s_pair = reinterpret_cast<const uint16_t *>(&s_lds[wave][my_sel][slot0]);
     const uint32_t *t_rel = &t_lds[wave][my_sel * 8];
@@ -254,8 +274,11 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     }
 
     // The activation loads were issued before the per-tile words that the code above has waited for,
-    // and loads complete in order: they have landed.
-    __syncthreads();
+    // and loads complete in order: this wave's have landed, and after the barrier every wave's.  A bare
+    // barrier: the usual one first waits for every outstanding load, and the plane-L ring should stay
+    // in flight across it.  (Everything else in LDS is private to the wave that wrote it.)
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
 
     float4_t acc[MT];
 #pragma unroll
