@@ -165,10 +165,22 @@ def main() -> int:
         fgmp.quantize_activations(xd, fxd, Tx, sx, out=pX)
         fgmp.gemm(pX, pW, out=Y, workspace=ws)
     ms_unfused = timed(unfused, args.steps, 20)
+    # reference rates measured on this device: a loop of independent FP16 MFMAs (2 waves per SIMD) and a
+    # device-to-device copy (bytes read + written)
+    sink = torch.empty(1024 * 256, dtype=torch.float32, device=dev)
+    ms_mfma = timed(lambda: fgmp.selftest_mfma_rate(1024, 2000, sink), 20, 5)
+    mfma_loop_tflops = 1024 * 4 * 2000 * 8 * 32768.0 / (ms_mfma * 1e-3) / 1e12
+    src_c = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).zero_()
+    dst_c = torch.empty_like(src_c)
+    ms_copy = timed(lambda: dst_c.copy_(src_c), 20, 5)
+    copy_gbps = 2.0 * src_c.numel() / (ms_copy * 1e-3) / 1e9
+    del sink, src_c, dst_c
+    reference = {"mfma_loop_TFLOPs": round(mfma_loop_tflops, 1), "device_copy_GBps": round(copy_gbps, 1)}
     roofline = {"bound": "mfma", "kernel": "gemm_mixed_kernel", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
                 "traffic": GEMM_KERNEL_HBM_BYTES, "ms_per_launch": round(ms_kernel, 4),
                 "ms_quantize_to_f16": round(ms_quant16, 4),
+                "frac_of_measured_mfma_loop": round(achieved / mfma_loop_tflops, 4),
                 "gemm_call_alone": {"ms": round(ms_gemm, 4), "TFLOPs": round(flops / (ms_gemm * 1e-3) / 1e12, 2)}}
 
     out = {
@@ -182,6 +194,7 @@ def main() -> int:
                    "fp8_fraction_x": round(x_info["n_fp8_blocks"] / x_info["n_blocks"], 4),
                    "packed_w_bytes": w_info["bytes_used"]},
         "roofline": roofline,
+        "reference_rates": reference,
     }
 
     extra = {"ms_quantize_x": round(ms_quant, 4), "ms_gemm": round(ms_gemm, 4), "host_ms_per_step": round(t_host, 4),
@@ -206,6 +219,7 @@ def main() -> int:
         gbps = qbytes / (ms_q * 1e-3) / 1e9
         extra["act_quant_16384x8192"] = {"ms": round(ms_q, 4), "GBps": round(gbps, 1),
                                          "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
+                                         "frac_of_measured_copy": round(gbps / copy_gbps, 4),
                                          "algorithmic_bytes": int(qbytes)}
         # the same pass with the Eq. 8 score (error increase of NVFP4 over FP8): threshold recalibrated for 10%
         _, sc = fgmp.quantize_activations(xqd, fq, float("inf"), sq, want_scores=True, score_mode="delta")
@@ -271,6 +285,7 @@ def main() -> int:
                 dec[f"{name}_K{Kd}_N{Nd}_M{Md}"] = {
                     "us_per_step": round(ms_d * 1e3, 2), "GBps": round(dbytes / (ms_d * 1e-3) / 1e9, 1),
                     "frac_hbm_peak": round(dbytes / (ms_d * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                    "frac_of_measured_copy": round(dbytes / (ms_d * 1e-3) / 1e9 / copy_gbps, 4),
                     "us_gemm_from_packed_x": round(ms_g * 1e3, 2), "packed_w_bytes": used}
             del pool
         extra["decode_hbm_cold"] = dec
@@ -413,12 +428,21 @@ def main() -> int:
         rows = int(min(M, max(128, budget // cols)))
         dt = oracle_step(rows, cols)
         cpu_flops = 2.0 * rows * cols * K
+        # the same on one thread, on a sample smaller by the thread count (about the same wall time)
+        n_thr = orc.num_threads()
+        rows1 = max(8, rows // max(n_thr, 1))
+        orc.set_num_threads(1)
+        dt1 = oracle_step(rows1, cols)
+        orc.set_num_threads(n_thr)
         out["cpu_baseline"] = {"value": round(cpu_flops / dt / 1e12, 6), "unit": "TFLOP/s",
                                "cores": orc.num_threads(), "kind": "oracle",
                                "sample": f"the same step on the first {rows} rows of X (score, quantize, dequantize) "
                                          f"times the first {cols} weight rows at full K={K}, fp64 dot products; "
                                          f"{dt:.1f} s; rate = 2*rows*cols*K / time",
-                               "seconds": round(dt, 2)}
+                               "seconds": round(dt, 2),
+                               "one_thread": {"value": round(2.0 * rows1 * cols * K / dt1 / 1e12, 6), "unit": "TFLOP/s",
+                                              "sample": f"first {rows1} rows of X times the first {cols} weight rows",
+                                              "seconds": round(dt1, 2)}}
 
     print(json.dumps(out), flush=True)
     return 0

@@ -274,6 +274,16 @@ fgmp_status_t fgmp_selftest_encode_ranges(int format, uint32_t *min_bits, uint32
                                           uint32_t *violations, void *stream);
 fgmp_status_t fgmp_selftest_decode_table(int format, float *out, void *stream);
 
+/*
+ * Measurement reference: a loop of nothing but independent dense FP16 matrix
+ * instructions (32x32x16, FP32 accumulate) -- the rate the prefill GEMM's
+ * roofline fraction can also be quoted against.  Launches `workgroups`
+ * workgroups of 4 waves, each wave issuing 8 * iters instructions (32768 flops
+ * each); the caller times the launch.  sink: device, workgroups * 256 floats,
+ * written once at the end (keeps the arithmetic alive).
+ */
+fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -438,3 +438,9 @@ int64_t fgmp_oracle_storage_bits(int64_t n_lo, int64_t n_hi)
 
 /* Threads the OpenMP loops above will use (reported beside timings). */
 int fgmp_oracle_num_threads(void) { return omp_get_max_threads(); }
+
+/* Number of threads for the loops above from now on (for timing the oracle on one core). */
+void fgmp_oracle_set_num_threads(int n)
+{
+    if (n > 0) omp_set_num_threads(n);
+}

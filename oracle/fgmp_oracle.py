@@ -73,6 +73,8 @@ def _load():
     lib.fgmp_oracle_storage_bits.argtypes = [i64, i64]
     lib.fgmp_oracle_num_threads.restype = ctypes.c_int
     lib.fgmp_oracle_num_threads.argtypes = []
+    lib.fgmp_oracle_set_num_threads.restype = None
+    lib.fgmp_oracle_set_num_threads.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
 
@@ -200,3 +202,8 @@ def storage_bits(n_lo: int, n_hi: int) -> int:
 def num_threads() -> int:
     """Threads the OpenMP loops of the oracle will use."""
     return int(_load().fgmp_oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the OpenMP loops of the oracle use from now on."""
+    _load().fgmp_oracle_set_num_threads(int(n))

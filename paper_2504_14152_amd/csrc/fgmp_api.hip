@@ -232,4 +232,9 @@ fgmp_status_t fgmp_selftest_decode_table(int format, float *out, void *stream)
     return selftest_decode_table(format, out, as_stream(stream));
 }
 
+fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, void *stream)
+{
+    return selftest_mfma_rate(workgroups, iters, sink, as_stream(stream));
+}
+
 }  // extern "C"

@@ -406,4 +406,38 @@ fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, i
                            scores_y, /*compact=*/false, st);
 }
 
+// Measurement reference: independent MFMAs only (8 accumulators per wave, so no instruction waits for
+// the previous one's result).
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float *sink, int iters)
+{
+    half8_t a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (_Float16)(0.001f * (float)(threadIdx.x & 63) + (float)i);
+        b[i] = (_Float16)(0.5f * (float)i);
+    }
+    float16_t acc[8];
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[n][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[n], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[n][r];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+fgmp_status_t selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, hipStream_t st)
+{
+    if (!sink || workgroups <= 0 || workgroups > 0x7FFFFFFF || iters <= 0) return FGMP_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(256), 0, st, sink, (int)iters);
+    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+}
+
 }  // namespace fgmp

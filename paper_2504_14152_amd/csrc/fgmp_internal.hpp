@@ -82,5 +82,6 @@ void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, con
 fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);
+fgmp_status_t selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, hipStream_t st);
 
 }  // namespace fgmp

@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
     L.fgmp_selftest_encode_ranges.argtypes = [ctypes.c_int, vp, vp, vp, vp]
     L.fgmp_selftest_decode_table.restype = ctypes.c_int
     L.fgmp_selftest_decode_table.argtypes = [ctypes.c_int, vp, vp]
+    L.fgmp_selftest_mfma_rate.restype = ctypes.c_int
+    L.fgmp_selftest_mfma_rate.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp]
     _lib = L
     return L
 
@@ -331,6 +333,12 @@ def selftest_encode_ranges(fmt: int, device="cuda"):
     torch.cuda.synchronize()
     to_u32 = lambda t: t.cpu().numpy().view("uint32")
     return to_u32(mn), to_u32(mx), int(to_u32(viol)[0])
+
+
+def selftest_mfma_rate(workgroups: int, iters: int, sink: torch.Tensor) -> None:
+    """Launch the pure-MFMA reference loop (the caller times it); sink: workgroups * 256 floats."""
+    assert sink.dtype == torch.float32 and sink.numel() >= workgroups * 256
+    _check(lib().fgmp_selftest_mfma_rate(int(workgroups), int(iters), _ptr(sink), _stream()), "fgmp_selftest_mfma_rate")
 
 
 def selftest_decode_table(fmt: int, device="cuda"):
