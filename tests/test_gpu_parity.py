@@ -647,3 +647,13 @@ def test_gemm_two_pass_path_in_subprocess():
     env = dict(os.environ, FGMP_PREFILL_KERNEL="dense")
     res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110)
     assert res.returncode == 0 and "two-pass ok" in res.stdout, res.stdout + res.stderr
+
+
+def test_mfma_rate_reference_runs():
+    """The benchmark's reference loop: launches, finishes, and its arithmetic is kept (finite sums)."""
+    _say("mfma rate reference")
+    sink = torch.full((64 * 256,), float("nan"), dtype=torch.float32, device=DEV)
+    fgmp.selftest_mfma_rate(64, 50, sink)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
+
