@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_f16_kernel(const _Float
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / kWN, wn = wave % kWN;
     int64_t tm, tn;
-    tile_coords(n_tm, n_tn, tm, tn);
+    tile_coords(blockIdx.x, n_tm, n_tn, tm, tn);
 
     // direct global -> LDS: wave-load j (j = kWaves i + wave) fills tile rows 8 j .. 8 j + 7;
     // lane (lr = lane / 8, c = lane % 8) fetches global chunk c ^ swizzle(row) of its row;
@@ -210,7 +210,7 @@ static inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * 
 
 struct GemmWorkspace {
     int64_t ld, Mp, Np;
-    size_t off_a, off_b, total;
+    size_t off_a, off_b, off_split, total;   // off_split: partial tiles and counters of a split last round
 };
 
 static GemmWorkspace gemm_ws_layout(int64_t M, int64_t N, int64_t K)
@@ -221,7 +221,8 @@ static GemmWorkspace gemm_ws_layout(int64_t M, int64_t N, int64_t K)
     w.Np = round_up(N, kBN);
     w.off_a = 0;
     w.off_b = (size_t)align_up((uint64_t)w.Mp * w.ld * 2, 256);
-    w.total = w.off_b + (size_t)align_up((uint64_t)w.Np * w.ld * 2, 256);
+    w.off_split = w.off_b + (size_t)align_up((uint64_t)w.Np * w.ld * 2, 256);
+    w.total = w.off_split + gemm_mixed_split_bytes((w.Mp / kBM) * (w.Np / kBN));
     return w;
 }
 
@@ -291,9 +292,10 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
         const int64_t tiles_m = w.Mp / kBM, tiles_n = w.Np / kBN;
         if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
         const DecodeJob jx = make_decode_job(A, la, x16, w.ld, w.Mp / kTileRows);
-        const fgmp_status_t rcx = launch_decode_f16(jx, nullptr, nullptr, 0, st);
+        const SplitTail sp = plan_split_tail(tiles_m * tiles_n, (int)(w.ld / kBK), static_cast<char *>(workspace) + w.off_split);
+        const fgmp_status_t rcx = launch_decode_f16(jx, nullptr, sp.counters, (int64_t)sp.n_split, st);
         if (rcx != FGMP_OK) return rcx;
-        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, A.hdr, st);
+        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, A.hdr, st, sp);
         return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
     }
     _Float16 *a16 = reinterpret_cast<_Float16 *>(static_cast<char *>(workspace) + w.off_a);
@@ -347,13 +349,15 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
         if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
         PackedHeader *hx = reinterpret_cast<PackedHeader *>(ws);
         _Float16 *x16 = reinterpret_cast<_Float16 *>(ws + kHeaderBytes);
+        char *split_region = ws + (size_t)make_layout(M, K).total_bytes + w.off_split;
+        const SplitTail sp = plan_split_tail(tiles_m * tiles_n, (int)(w.ld / kBK), split_region);
         const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws,
-                                                 sizeof(PackedHeader), nullptr, false, st, x16, w.ld, nullptr, 0,
-                                                 score_mode);
+                                                 sizeof(PackedHeader), nullptr, false, st, x16, w.ld, sp.counters,
+                                                 (int64_t)sp.n_split, score_mode);
         if (rc != FGMP_OK) return rc;
         const PackedLayout lb = make_layout(N, K);
         const PackedView B = make_view(const_cast<void *>(packed_W), lb);
-        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, hx, st, pack_out);
+        launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, hx, st, sp, pack_out);
         return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
     }
     const size_t xbytes = (size_t)make_layout(M, K).total_bytes;

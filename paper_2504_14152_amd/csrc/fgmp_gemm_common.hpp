@@ -11,6 +11,26 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kNumXcd = 8;
 
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// partial sums that workgroups on different XCDs exchange
+// ---------------------------------------------------------------------------
+
+// 16-byte accesses to a partial-sum buffer that are coherent across XCDs: buffer instructions with
+// the sc0 sc1 cache policy (system scope) bypass the per-XCD L2; being ordinary loads and stores,
+// the compiler tracks their completion itself.
+constexpr int kCoherent = 1 | 16;   // sc0 | sc1
+__device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off, float4_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), buf, (int)byte_off, 0, kCoherent);
+}
+__device__ __forceinline__ float4_t load_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off)
+{
+    return __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(buf, (int)byte_off, 0, kCoherent));
+}
+
 // ---------------------------------------------------------------------------
 // packed -> FP16 decode
 // ---------------------------------------------------------------------------
@@ -60,17 +80,16 @@ constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kRowBytes = kBK * 2;               // 128 B of K per tile row, 8 chunks of 16 B
 constexpr int kTileBytes = kBM * kRowBytes;      // 32 KB per operand per stage
 
-// Map the hardware workgroup id (dispatched round-robin over the 8 XCDs) to a
+// Map the hardware workgroup id `id` (dispatched round-robin over the 8 XCDs) to a
 // logical tile id so that each XCD works on a contiguous range of tiles, then
 // to (tile_m, tile_n) in groups of 4 M-tiles so that concurrently running
 // workgroups share operand tiles in their XCD's L2: the 32 workgroups an XCD
 // runs at a time then cover 4 x 8 tiles, i.e. 4 row panels of A and 8 of the
 // packed weights per pass over K (groups of 8 fetch a fifth more, groups of 16
 // run 4% slower).
-__device__ __forceinline__ void tile_coords(int64_t n_tm, int64_t n_tn, int64_t &tm, int64_t &tn)
+__device__ __forceinline__ void tile_coords(int64_t id, int64_t n_tm, int64_t n_tn, int64_t &tm, int64_t &tn)
 {
     const int64_t n = n_tm * n_tn;
-    const int64_t id = blockIdx.x;
     const int64_t xcd = id % kNumXcd, idx = id / kNumXcd;
     const int64_t q = n / kNumXcd, rem = n % kNumXcd;
     const int64_t logical = xcd * q + (xcd < rem ? xcd : rem) + idx;

@@ -31,7 +31,6 @@
 
 namespace fgmp {
 
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 // Per thread and K-step: the plane-L words (needed when the step is decoded) and the small fields
@@ -86,10 +85,10 @@ template <int kPending, int kBPT> __device__ __forceinline__ void wait_loaded(u3
 // the paper (Sec. 4.2): results are quantized before they leave for memory.
 template <int kWM, int kWN, bool kPackOut>
 __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Float16 *__restrict__ A, int64_t ld,
-                                                                       PackedView W, PackedLayout lw, int nk,
+                                                                       PackedView W, PackedLayout lw, int nk_total,
                                                                        float *__restrict__ Y, int64_t ldy, int64_t M,
                                                                        int64_t N, int64_t n_tm, int64_t n_tn,
-                                                                       const PackedHeader *ha, PackOut po)
+                                                                       const PackedHeader *ha, PackOut po, SplitTail sp)
 {
     constexpr int kWaves = kWM * kWN;
     static_assert(kWaves == 8 || kWaves == 4, "the weight decode assigns 2 (512 threads) or 4 (256 threads) blocks per K-step to a thread");
@@ -102,14 +101,22 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / kWN, wn = wave % kWN;
+    // Workgroups [0, n_whole) compute one tile each over all of K.  The tiles beyond -- a last, partly
+    // filled round of the chip -- are split in two along K: workgroup n_whole + u takes tile
+    // n_whole + u % n_split, K-steps [0, kt_split) if u < n_split and [kt_split, nk_total) otherwise.
     int64_t tm, tn;
-    tile_coords(n_tm, n_tn, tm, tn);
+    const int unit = (int)blockIdx.x - sp.n_whole;
+    const bool split = unit >= 0;
+    const int split_tile = split ? unit % sp.n_split : 0, upper = split && unit >= sp.n_split;
+    tile_coords(split ? sp.n_whole + split_tile : (int64_t)blockIdx.x, n_tm, n_tn, tm, tn);
+    const int kt0 = upper ? sp.kt_split : 0;                                    // first K-step of this workgroup
+    const int nk = split ? (upper ? nk_total - sp.kt_split : sp.kt_split) : nk_total;   // and how many
 
     // ---- A: direct global -> LDS, chunk swizzle applied on the global side.  The address is a uniform
     // base (tile row, K-step) plus a per-lane 32-bit offset that never changes, so the loop spends no
     // vector instructions on it. ----
     const int lr = lane >> 3, lc = (lane & 7) ^ (((wave * 8 + lr) >> 1) & 7);
-    const char *a_tile = reinterpret_cast<const char *>(A + tm * kBM * ld);
+    const char *a_tile = reinterpret_cast<const char *>(A + tm * kBM * ld) + (int64_t)kt0 * kRowBytes;
     const uint32_t a_off = (uint32_t)((wave * 8 + lr) * ld * 2 + lc * 16);
     const int64_t a_step = (int64_t)kWaves * 8 * ld * 2;   // load i fetches rows 8 kWaves i + ...
     auto issue_a = [&](int kt, int stage) {
@@ -138,8 +145,8 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     const uint32_t rt_b = (uint32_t)((row_b >> 3) < lw.n_rt ? (row_b >> 3) : lw.n_rt - 1);
     const int r8 = (int)(row_b & 7);
     const int swz_b = (br >> 1) & 7;
-    const int last_kt = nk - 1;
-    const uint32_t tile_b = rt_b * (uint32_t)lw.n_kt;                       // first tile of the thread's row-tile
+    const int last_kt = nk_total - 1 - kt0;   // K-steps count from the workgroup's first one; kt0 is even
+    const uint32_t tile_b = rt_b * (uint32_t)lw.n_kt + (uint32_t)(kt0 >> 1);   // first tile of the thread's row-tile in this workgroup's K range
     const uint32_t vL = (uint32_t)lw.off_L + (tile_b * kTileSlots + r8 * kTileBlocks + 2 * bp) * 8u;
     const uint32_t vS = (uint32_t)lw.off_S + tile_b * kTileSlots + r8 * kTileBlocks + 2 * bp;
     const uint32_t vM = (uint32_t)lw.off_M + tile_b * 8u + (r8 < 4 ? 0u : 4u);   // rows 0-3 of a tile: low half of its mask word
@@ -329,6 +336,52 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
 
     const bool w_ok = W.hdr->magic == kMagic && W.hdr->rows == lw.rows && W.hdr->K == lw.K;
     const float ss = w_ok ? ha->tensor_scale * W.hdr->tensor_scale : 0.0f;
+    if (split) {
+        // The two parts of a tile meet here.  A workgroup that finds the tile's counter at 1 knows the
+        // other part's accumulators are in memory, complete: it adds them to its own and goes on to the
+        // epilogue.  Otherwise every wave stores its accumulators (layout [tile][part][wave][register
+        // quad][lane], 16 bytes per lane and store); when all of the workgroup's stores are complete, one
+        // thread bumps the counter; if the other part arrived meanwhile (both stored), the workgroup that
+        // bumped second finishes the tile, the other one is done.  a + b = b + a exactly, so the result does
+        // not depend on the order of arrival.  The first part is the shorter one and is launched first, so
+        // it normally is in memory when the second needs it, off the critical path.  Partials and counter
+        // cross XCDs: system-coherent accesses that bypass the per-XCD L2.
+        constexpr uint32_t kWaveBytes = TM * TN * 4 * 1024;
+        const __amdgpu_buffer_rsrc_t pbuf =
+            __builtin_amdgcn_make_buffer_rsrc(sp.partial, 0, (int)sp.partial_bytes, 0x00020000);
+        const uint32_t mine = (uint32_t)((split_tile * 2 + upper) * kWaves + wave) * kWaveBytes + lane * 16u;
+        const uint32_t other = (uint32_t)((split_tile * 2 + (upper ^ 1)) * kWaves + wave) * kWaveBytes + lane * 16u;
+        uint32_t *arrived = reinterpret_cast<uint32_t *>(&lds[0][0][0]);   // the operand stages are free now
+        __syncthreads();
+        if (tid == 0) *arrived = __hip_atomic_load(&sp.counters[split_tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*arrived == 0u) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        store_coherent16(pbuf, mine + ((i * TN + j) * 4 + q) * 1024u,
+                                         float4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]});
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();   // all stores of the workgroup are complete (and everyone has read *arrived)
+            if (tid == 0)
+                *arrived = __hip_atomic_fetch_add(&sp.counters[split_tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (*arrived == 0u) return;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4_t o = load_coherent16(pbuf, other + ((i * TN + j) * 4 + q) * 1024u);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
+                }
+    }
     if constexpr (!kPackOut) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -419,27 +472,68 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
                 po.out.T[tile] = (uint32_t)(tile * kTileSlots);
             }
         }
-        if (blockIdx.x == 0 && tid == 0) write_header(po.out.hdr, ly, po.S, 0u);
+        // the header: by the workgroup that completes the first tile of the launch order
+        const int first_tile = split ? sp.n_whole + split_tile : (int)blockIdx.x;
+        if (first_tile == 0 && tid == 0) write_header(po.out.hdr, ly, po.S, 0u);
     }
+}
+
+// A tile keeps a compute unit busy for one "round"; the chip runs kNumCu tiles per round.  When the
+// last round is at most half full, its tiles are split in two along K: two half-length workgroups per
+// tile still fit one round, which then takes half the time (4096 x 22016: 1376 tiles = 5 rounds + 96
+// tiles; 6 rounds become 5.5).  Fuller last rounds, and K ranges too short to halve, are left alone.
+constexpr int64_t kNumCu = 256;
+constexpr size_t kSplitTileBytes = 2 * (size_t)kBM * kBN * 4;          // both halves' accumulators of one tile
+
+static int64_t split_tiles(int64_t n_tiles)
+{
+    const int64_t tail = n_tiles % kNumCu;
+    return tail <= kNumCu / 2 ? tail : 0;
+}
+
+size_t gemm_mixed_split_bytes(int64_t n_tiles)
+{
+    const int64_t n = split_tiles(n_tiles);
+    return n == 0 ? 0 : (size_t)n * kSplitTileBytes + (size_t)align_up((uint64_t)n * 4, 256);
+}
+
+SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region)
+{
+    SplitTail sp{};
+    const int64_t n = split_tiles(n_tiles);
+    if (n == 0 || nk < 4 || region == nullptr) {
+        sp.n_whole = (int)n_tiles;
+        return sp;
+    }
+    sp.n_whole = (int)(n_tiles - n);
+    sp.n_split = (int)n;
+    // even (a K-step pair is one 128-element tile of the packed layout), and somewhat less than half: the
+    // first part is done, and in memory, before the second one asks for it
+    sp.kt_split = ((nk * 7 / 16) & ~1) >= 2 ? (nk * 7 / 16) & ~1 : 2;
+    sp.partial_bytes = (uint32_t)((size_t)n * kSplitTileBytes);
+    sp.partial = static_cast<float *>(region);
+    sp.counters = reinterpret_cast<uint32_t *>(static_cast<char *>(region) + sp.partial_bytes);
+    return sp;
 }
 
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
-                       hipStream_t st, const PackOut *pack_out)
+                       hipStream_t st, const SplitTail &sp, const PackOut *pack_out)
 {
+    const unsigned grid = (unsigned)(sp.n_whole + 2 * sp.n_split);
 #ifndef FGMP_MIXED_WM
 #define FGMP_MIXED_WM 2
 #define FGMP_MIXED_WN 4
 #endif
     constexpr int kThreads = FGMP_MIXED_WM * FGMP_MIXED_WN * 64;
     if (pack_out != nullptr)
-        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, true>), dim3((unsigned)(n_tm * n_tn)),
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, true>), dim3(grid),
                            dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
-                           *pack_out);
+                           *pack_out, sp);
     else
-        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false>), dim3((unsigned)(n_tm * n_tn)),
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false>), dim3(grid),
                            dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
-                           PackOut{});
+                           PackOut{}, sp);
 }
 
 }  // namespace fgmp

@@ -34,8 +34,6 @@
 
 namespace fgmp {
 
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 // K-tiles per workgroup and plane-H entries staged per row-tile and K range (FP8 blocks beyond fetch
@@ -50,19 +48,6 @@ constexpr int kSkSumPass = 4;     // partial tiles summed per pass (their loads 
 constexpr int kSkMaxSplit = 16;   // most K ranges per row group the planner asks for
 
 constexpr uint32_t kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
-
-// 16-byte accesses to the partial-sum buffer that are coherent across XCDs: buffer instructions with
-// the sc0 sc1 cache policy (system scope) bypass the per-XCD L2; being ordinary loads and stores,
-// the compiler tracks their completion itself.
-constexpr int kCoherent = 1 | 16;   // sc0 | sc1
-__device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off, float4_t v)
-{
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), buf, (int)byte_off, 0, kCoherent);
-}
-__device__ __forceinline__ float4_t load_coherent16(__amdgpu_buffer_rsrc_t buf, uint32_t byte_off)
-{
-    return __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(buf, (int)byte_off, 0, kCoherent));
-}
 
 __device__ __forceinline__ uint4 ld128(__amdgpu_buffer_rsrc_t b, uint32_t off, uint32_t soff = 0)
 {

@@ -76,9 +76,23 @@ struct PackOut {
     float T, S;            // threshold and tensor scale of the output tensor
     float *scores;         // nullable, M * N / 16
 };
+// The last, partly filled round of tiles of the prefill kernel, split in two along K (n_split 0: no split).
+struct SplitTail {
+    int n_whole;              // workgroups [0, n_whole) compute whole tiles
+    int n_split;              // tiles n_whole .. n_whole + n_split - 1 are computed by two workgroups each
+    int kt_split;             // the first covers K-steps [0, kt_split), the second the rest (kt_split even)
+    uint32_t partial_bytes;   // n_split * 2 * 256 KB
+    float *partial;           // accumulators of the halves, 16-byte aligned
+    uint32_t *counters;       // n_split arrival counters, zero at launch
+};
+// Workspace bytes the split of `n_tiles` output tiles needs (0: no split), and the split itself with its
+// buffers at `region` (that many bytes, 256-byte aligned); `nk` K-steps of 64.
+size_t gemm_mixed_split_bytes(int64_t n_tiles);
+SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region);
+// `sp.counters` (sp.n_split words) must be zero when the kernel starts
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
-                       hipStream_t st, const PackOut *pack_out = nullptr);
+                       hipStream_t st, const SplitTail &sp, const PackOut *pack_out = nullptr);
 fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);

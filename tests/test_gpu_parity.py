@@ -413,11 +413,12 @@ def test_fused_packed_output_matches_oracle(M, K, N):
     assert np.all(np.abs(Z.cpu().numpy().astype(np.float64) - zw) <= tol)
 
 
-def test_packed_output_on_random_inputs_is_consistent():
+@pytest.mark.parametrize("M,K,N", [(200, 512, 272), (4352, 256, 4096)])
+def test_packed_output_on_random_inputs_is_consistent(M, K, N):
     """On ordinary inputs the FP32 results differ from the oracle's fp64 product in the last bits, so
     codes cannot be compared one by one; the epilogue must still equal the standalone quantizer run on
-    the very FP32 results the plain fused call writes (same arithmetic, same values)."""
-    M, K, N = 200, 512, 272
+    the very FP32 results the plain fused call writes (same arithmetic, same values).  The second shape
+    has whole tiles and tiles computed in two parts along K in one launch."""
     c = _quantized_pair(M, K, N, 33, 0.1, per_elem_w=False)
     f_n = torch.from_numpy(synth.fisher_per_channel(N, 33, 9)).to(DEV)
     Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
@@ -572,6 +573,25 @@ def test_fused_prefill_saturating_tensor_scale(dtype):
     _check_gemm(c, Yf, label=f"fused saturating {dtype}")
     Y = fgmp.gemm(fgmp.quantize_activations(xd, fxd, Tx, sx), pW)
     assert torch.equal(Y, Yf)
+
+
+def test_gemm_split_last_round_sampled():
+    """272 output tiles: 256 computed whole, the 16 of the partly filled last round in two parts along K
+    (2 + 6 K-steps) that meet through the workspace.  Rows and columns are drawn from every tile."""
+    M, K, N = 4352, 512, 4096
+    _say("gemm 4352x512x4096: whole tiles and split tiles in one launch")
+    c = _quantized_pair(M, K, N, 11, 0.2, per_elem_w=False)
+    Y = fgmp.gemm(c["pX"], c["pW"])
+    rng = np.random.default_rng(77)
+    rows = np.sort(np.concatenate([t * 256 + rng.choice(256, 3, replace=False) for t in range(M // 256)]))
+    cols = np.sort(np.concatenate([t * 256 + rng.choice(256, 16, replace=False) for t in range(N // 256)]))
+    _check_gemm(c, Y, rows, cols, label="whole + split tiles")
+    assert torch.isfinite(Y).all()
+    Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    assert torch.equal(Y, Yf)
+    # the parts of a tile may arrive in either order: a + b = b + a, so repeated calls agree bit for bit
+    for _ in range(3):
+        assert torch.equal(Yf, fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"]))
 
 
 def test_gemm_fc2_shape_sampled():
