@@ -287,6 +287,18 @@ fgmp_status_t fgmp_selftest_decode_table(int format, float *out, void *stream);
  */
 fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, void *stream);
 
+/*
+ * Measurement hook: the duration of the prefill GEMM kernel inside a fused
+ * call.  While a pair of HIP events (hipEvent_t, created by the caller with
+ * timing enabled) is set, every launch of that kernel records `ev_start` on
+ * its stream immediately before the launch and `ev_stop` immediately after;
+ * the caller synchronizes and reads hipEventElapsedTime.  Two null pointers
+ * clear the hook; one null and one non-null pointer is FGMP_ERR_INVALID_ARG.
+ * The pair is process-wide state, not synchronized: for single-threaded
+ * measurement code only.
+ */
+fgmp_status_t fgmp_selftest_time_gemm_kernel(void *ev_start, void *ev_stop);
+
 #ifdef __cplusplus
 }
 #endif

@@ -237,4 +237,11 @@ fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *
     return selftest_mfma_rate(workgroups, iters, sink, as_stream(stream));
 }
 
+fgmp_status_t fgmp_selftest_time_gemm_kernel(void *ev_start, void *ev_stop)
+{
+    if ((ev_start == nullptr) != (ev_stop == nullptr)) return FGMP_ERR_INVALID_ARG;
+    set_gemm_kernel_events(static_cast<hipEvent_t>(ev_start), static_cast<hipEvent_t>(ev_stop));
+    return FGMP_OK;
+}
+
 }  // extern "C"

@@ -516,10 +516,18 @@ SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region)
     return sp;
 }
 
+static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;   // measurement hook
+void set_gemm_kernel_events(hipEvent_t start, hipEvent_t stop)
+{
+    g_ev_start = start;
+    g_ev_stop = stop;
+}
+
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
                        hipStream_t st, const SplitTail &sp, const PackOut *pack_out)
 {
+    if (g_ev_start) (void)hipEventRecord(g_ev_start, st);
     const unsigned grid = (unsigned)(sp.n_whole + 2 * sp.n_split);
 #ifndef FGMP_MIXED_WM
 #define FGMP_MIXED_WM 2
@@ -534,6 +542,7 @@ void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, con
         hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false>), dim3(grid),
                            dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
                            PackOut{}, sp);
+    if (g_ev_stop) (void)hipEventRecord(g_ev_stop, st);
 }
 
 }  // namespace fgmp

@@ -88,6 +88,8 @@ def lib() -> ctypes.CDLL:
     L.fgmp_selftest_decode_table.argtypes = [ctypes.c_int, vp, vp]
     L.fgmp_selftest_mfma_rate.restype = ctypes.c_int
     L.fgmp_selftest_mfma_rate.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp]
+    L.fgmp_selftest_time_gemm_kernel.restype = ctypes.c_int
+    L.fgmp_selftest_time_gemm_kernel.argtypes = [vp, vp]
     _lib = L
     return L
 
@@ -339,6 +341,17 @@ def selftest_mfma_rate(workgroups: int, iters: int, sink: torch.Tensor) -> None:
     """Launch the pure-MFMA reference loop (the caller times it); sink: workgroups * 256 floats."""
     assert sink.dtype == torch.float32 and sink.numel() >= workgroups * 256
     _check(lib().fgmp_selftest_mfma_rate(int(workgroups), int(iters), _ptr(sink), _stream()), "fgmp_selftest_mfma_rate")
+
+
+def selftest_time_gemm_kernel(start: "torch.cuda.Event | None", stop: "torch.cuda.Event | None") -> None:
+    """Set (or, with None, clear) the pair of timing events the library records around every launch of
+    the prefill GEMM kernel.  The events must have been recorded once already (torch creates the HIP
+    event on first use)."""
+    hs = 0 if start is None else int(start.cuda_event)
+    he = 0 if stop is None else int(stop.cuda_event)
+    if (start is not None and hs == 0) or (stop is not None and he == 0):
+        raise FgmpError("timing events must be recorded once before they are handed to the library")
+    _check(lib().fgmp_selftest_time_gemm_kernel(hs or None, he or None), "fgmp_selftest_time_gemm_kernel")
 
 
 def selftest_decode_table(fmt: int, device="cuda"):

@@ -40,6 +40,9 @@ def test_sizes_and_host_side_argument_checks():
     assert L.fgmp_quantize_activations(None, 0, 8, 128, 128, None, 0.0, 1.0, None, 0, None, None) == -1
     # measurement helper: no sink, no work
     assert L.fgmp_selftest_mfma_rate(256, 10, None, None) == -1
+    # measurement hook: a lone event is refused, clearing always works
+    assert L.fgmp_selftest_time_gemm_kernel(256, None) == -1
+    assert L.fgmp_selftest_time_gemm_kernel(None, None) == 0
     assert L.fgmp_gemm(None, 1, None, 1, 16, None, 1, None, 0, None) == -1
     assert L.fgmp_gemm(256, 1, 256, 1, 24, 256, 1, 256, 0, None) == -2
     assert L.fgmp_unpack_canonical(None, 1, 16, None, None, None, None) == -1

@@ -677,3 +677,25 @@ def test_mfma_rate_reference_runs():
     torch.cuda.synchronize()
     assert bool(torch.isfinite(sink).all())
 
+
+def test_gemm_kernel_timing_hook():
+    """The measurement hook brackets the prefill GEMM kernel with the caller's events; cleared, it records nothing."""
+    c = _quantized_pair(300, 512, 264, 5, 0.1, per_elem_w=False)
+    ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ea.record()
+    eb.record()
+    torch.cuda.synchronize()
+    fgmp.selftest_time_gemm_kernel(ea, eb)
+    try:
+        Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    finally:
+        fgmp.selftest_time_gemm_kernel(None, None)
+    torch.cuda.synchronize()
+    ms = ea.elapsed_time(eb)
+    assert 0.0 < ms < 50.0
+    _check_gemm(c, Y, label="timed launch")
+    # with the hook cleared the events keep their timestamps
+    fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    torch.cuda.synchronize()
+    assert ea.elapsed_time(eb) == ms
+
