@@ -138,11 +138,15 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     const uint32_t s_tile0 = (rtA + (lane >> 5)) * a.n_kt + c0;
     const char *xg = reinterpret_cast<const char *>(a.x16) + (int64_t)c0 * (kTileK * 2);
     const int64_t x_row_bytes = a.ld16 * 2;
+    const int x_load_rows = __builtin_amdgcn_readfirstlane((int)a.M);
     // everything above only needs the kernel arguments; no load below waits for more than those
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- activations: 16 MT rows x (ncols * 128) halves, straight into LDS; one wave-load fills
-    // 1 KB = half a row of 8 K-tiles.  Chunks past the K range re-read the row's first chunk (never used).
+    // ---- activations: the M rows there are, (ncols * 128) halves each, straight into LDS; one wave-load
+    // fills 1 KB = half a row of 8 K-tiles.  The other rows of the 16 MT stay as the LDS happens to be:
+    // they only feed output rows that are never stored (every workgroup re-reads its slice of X from
+    // the L2; at M = 1 that is 2 KB instead of 32).  Chunks past the K range re-read the row's first
+    // chunk (never used).
     // Written as assembly: while a global->LDS load that the compiler knows of is pending, it turns
     // every wait for an ordinary load into vmcnt(0), and the start-up below lives on exact waits (the
     // plane-H window can be requested as soon as the plane-T words are here, with the plane-L ring
@@ -154,7 +158,7 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
         const int chunk = h * 64 + lane;
         const int src_chunk = chunk < ncols * (kTileK / 8) ? chunk : 0;
         // (a row of fewer than 8 K-tiles ends inside the second wave-load: the lanes beyond it stay out)
-        if (chunk < kSkMaxCols * (kTileK / 8)) {
+        if (chunk < kSkMaxCols * (kTileK / 8) && r < x_load_rows) {
             const uint32_t dst = (uint32_t)(uintptr_t)(lds_void_t *)&xs[r][h * 512];   // M0: the wave's LDS destination
             const uint32_t voff = (uint32_t)(r * x_row_bytes + src_chunk * 16);
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(xg) : "memory");
