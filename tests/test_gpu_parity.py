@@ -594,6 +594,23 @@ def test_gemm_split_last_round_sampled():
         assert torch.equal(Yf, fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"]))
 
 
+def test_gemm_llama_fc1_prefill_sampled():
+    """The benchmark's FC1 shape and launch configuration: 1376 output tiles, 1280 computed whole and the
+    96 of the last round in two parts along K.  Sampled rows and columns (every 256-column tile gets
+    some) at full K."""
+    M, K, N = 4096, 4096, 22016
+    _say("gemm fc1 prefill 4096x4096x22016")
+    c = _quantized_pair(M, K, N, 2, 0.1, per_elem_w=False)
+    Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    rng = np.random.default_rng(321)
+    rows = np.sort(np.concatenate([t * 256 + rng.choice(256, 2, replace=False) for t in range(M // 256)]))
+    cols = np.sort(np.concatenate([t * 256 + rng.choice(256, 4, replace=False) for t in range(N // 256)]))
+    rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, N - 1
+    _check_gemm(c, Yf, rows, cols, label="fc1 prefill sampled")
+    assert torch.isfinite(Yf).all()
+    assert torch.equal(Yf, fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"]))
+
+
 def test_gemm_fc2_shape_sampled():
     M, K, N = 512, 11008, 4096
     _say("gemm fc2 512x11008x4096")
