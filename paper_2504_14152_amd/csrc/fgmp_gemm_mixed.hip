@@ -24,6 +24,11 @@
 // the register sets rotate by index (the loop body is instantiated for one
 // whole turn of the rotation), so a register that a load in flight will write
 // is never copied.
+//
+// One workgroup computes one 256 x 256 output tile over all of K -- except the
+// tiles of a last round that fills at most half of the chip: those are
+// computed by two workgroups each, over complementary K ranges, which meet
+// through the workspace after their loops (see SplitTail).
 #include <type_traits>
 
 #include "fgmp_gemm_common.hpp"
