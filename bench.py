@@ -417,6 +417,79 @@ def main() -> int:
                                               "fp8_fraction_y": round(fgmp.packed_info(pY)["n_fp8_blocks"] /
                                                                       (M * N // 16), 4)}
 
+    def gated_mlp():
+        """The gated MLP of a Llama-2-7B layer at M = 4096 (the FC1 / FC2 shapes of configs[2]): FC1 with its
+        22016 weight rows in groups of 32 gate + 32 up rows, SiLU(gate) * up and the output quantizer in
+        the GEMM epilogue (the 361 MB of FP32 results and the intermediate tensor never reach memory
+        unquantized), FC2 from the packed result.  Beside it the same work as two fused steps with FP32
+        results in between and the gate as a framework op."""
+        Mm, Kh, Nf, Nh = 4096, 4096, 22016, 11008
+        xg, xgb = dev_bf16(synth.activations(Mm, Kh, 0, 60))
+        sxg = float(synth.default_tensor_scale(synth.bf16_bits_to_f32(xgb)))
+        del xgb
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1060)
+        w1 = torch.empty((Nf, Kh), dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02, generator=gen)
+        w2 = torch.empty((Kh, Nh), dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02, generator=gen)
+        fx1 = torch.from_numpy(synth.fisher_per_channel(Kh, 0, 61)).to(dev)
+        fh = torch.from_numpy(synth.fisher_per_channel(Nh, 0, 62)).to(dev)
+        pws = []
+        for wt, fw in ((w1, fx1), (w2, fh)):
+            sw_ = float(wt.abs().max().float()) / 448.0
+            _, scw = fgmp.quantize_weights(wt, fw, float("inf"), sw_, want_scores=True)
+            pws.append(fgmp.quantize_weights(wt, fw, fgmp.threshold_for_fraction(scw, P_FP8), sw_))
+            del scw
+        del w1, w2
+        pW1, pW2 = pws
+        _, scx = fgmp.quantize_activations(xg, fx1, float("inf"), sxg, want_scores=True)
+        Txg = fgmp.threshold_for_fraction(scx, P_FP8)
+        del scx
+        # calibration of the intermediate tensor (scale, threshold) from one unfused pass
+        Y1 = torch.empty((Mm, Nf), dtype=torch.float32, device=dev)
+        ws1 = torch.empty(fgmp.workspace_bytes(Mm, Nf, Kh), dtype=torch.uint8, device=dev)
+        ws2 = torch.empty(fgmp.workspace_bytes(Mm, Kh, Nh), dtype=torch.uint8, device=dev)
+        Z = torch.empty((Mm, Kh), dtype=torch.float32, device=dev)
+
+        def framework_gate():
+            v = Y1.view(Mm, Nf // 64, 2, 32)
+            return (torch.nn.functional.silu(v[:, :, 0, :]) * v[:, :, 1, :]).reshape(Mm, Nh).to(torch.bfloat16)
+        fgmp.quant_gemm_fused(xg, fx1, Txg, sxg, pW1, out=Y1, workspace=ws1)
+        hb = framework_gate()
+        s_h = float(hb.abs().max().float()) / 448.0
+        _, sch = fgmp.quantize_activations(hb, fh, float("inf"), s_h, want_scores=True)
+        T_h = fgmp.threshold_for_fraction(sch, P_FP8)
+        del sch
+        pH = fgmp.quantize_activations(hb, fh, T_h, s_h)
+        ws_g = torch.empty(int(fgmp.lib().fgmp_workspace_bytes_packed_out_ex(Mm, Nf, Kh, fgmp.EPILOGUE_SILU_GATE)),
+                           dtype=torch.uint8, device=dev)
+
+        def fc1_gated():
+            fgmp.quant_gemm_fused_packed_out(xg, fx1, Txg, sxg, pW1, fh, T_h, s_h, out=pH, workspace=ws_g,
+                                             epilogue=fgmp.EPILOGUE_SILU_GATE)
+
+        def fc2_packed():
+            fgmp.gemm(pH, pW2, out=Z, workspace=ws2)
+
+        def both():
+            fc1_gated()
+            fc2_packed()
+
+        def unfused():
+            fgmp.quant_gemm_fused(xg, fx1, Txg, sxg, pW1, out=Y1, workspace=ws1)
+            h = framework_gate()
+            fgmp.quant_gemm_fused(h, fh, T_h, s_h, pW2, out=Z, workspace=ws2)
+        ms1, ms2, ms12, msu = timed(fc1_gated, 50, 10), timed(fc2_packed, 50, 10), timed(both, 50, 10), timed(unfused, 20, 5)
+        fl = 2.0 * Mm * Kh * Nf + 2.0 * Mm * Nh * Kh
+        fc1_gated()
+        ih = fgmp.packed_info(pH)
+        return {"ms_fc1_gate_quantize": round(ms1, 4), "ms_fc2_from_packed": round(ms2, 4), "ms_mlp": round(ms12, 4),
+                "TFLOPs": round(fl / (ms12 * 1e-3) / 1e12, 1),
+                "ms_mlp_fp32_between_and_framework_gate": round(msu, 4),
+                "fp8_fraction_h": round(ih["n_fp8_blocks"] / ih["n_blocks"], 4)}
+
+    if not args.no_extra:
+        extra["gated_mlp_llama2_7b_M4096"] = gated_mlp()
+
     if args.sweep:
         sw_res = {}
         for frac in (0.0, 0.1, 0.2, 0.3, 1.0):

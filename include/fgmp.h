@@ -58,6 +58,10 @@ typedef enum { FGMP_F32 = 0, FGMP_BF16 = 1 } fgmp_dtype_t;
  * The stored codes of a block depend only on the decision, not on the mode. */
 typedef enum { FGMP_SCORE_NVFP4_ERROR = 0, FGMP_SCORE_DELTA = 1 } fgmp_score_mode_t;
 
+/* Elementwise operator between the product and the output quantizer of
+ * fgmp_quant_gemm_fused_packed_out_ex (see there). */
+typedef enum { FGMP_EPILOGUE_NONE = 0, FGMP_EPILOGUE_SILU_GATE = 1 } fgmp_epilogue_t;
+
 /* Host-side summary of a packed tensor (fgmp_packed_info). */
 typedef struct {
     int64_t rows, K;
@@ -184,6 +188,31 @@ fgmp_status_t fgmp_quant_gemm_fused_packed_out(const void *X, fgmp_dtype_t dt, i
                                                float threshold_y, float scale_y, void *packed_Y,
                                                size_t packed_Y_bytes, float *scores_y, void *workspace,
                                                size_t workspace_bytes, void *stream);
+
+/*
+ * The same with an elementwise operator in front of the quantizer, so that the gated MLP of the models
+ * the paper evaluates (Sec. 5.1: FC1 = gate and up projection, FC2 = down projection) goes from FC1 to
+ * FC2 without its intermediate ever being stored unquantized.  FGMP_EPILOGUE_NONE: as above.
+ * FGMP_EPILOGUE_SILU_GATE: the N weight rows come in groups of 64 -- rows 64q .. 64q+31 are the gate
+ * rows of hidden units 32q .. 32q+31, rows 64q+32 .. 64q+63 their up rows -- and what is scored,
+ * quantized and packed is h = SiLU(g) * u per hidden unit, an M x N/2 tensor, with g and u the FP32
+ * numbers fgmp_quant_gemm_fused would have written.  The paper does not discuss the operator; since
+ * the codes depend on h to the last bit, h is a fixed sequence of FP32 operations, each rounded on its
+ * own: E(x) for x clamped to [-87, 88] is p * 2^n with n = rint(x * log2 e), r = (x - n * 0.693359375)
+ * - n * (ln 2 - 0.693359375) and p the degree-7 Taylor polynomial of e^r by Horner's rule;
+ * h = (g / (1 + E(-g))) * u with a correctly rounded division (within 3 ulp of the exact value).
+ *   N          N % 64 == 0 with the gate; fisher_n, scores_y and packed_Y then refer to N/2 columns
+ *   workspace  >= fgmp_workspace_bytes_packed_out_ex(M, N, K, epilogue)
+ * Other arguments and errors as fgmp_quant_gemm_fused_packed_out; an unknown `epilogue` is
+ * FGMP_ERR_INVALID_ARG.
+ */
+size_t fgmp_workspace_bytes_packed_out_ex(int64_t M, int64_t N, int64_t K, fgmp_epilogue_t epilogue);
+fgmp_status_t fgmp_quant_gemm_fused_packed_out_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                                  const float *fisher_k, float threshold, float scale_x,
+                                                  const void *packed_W, int64_t N, fgmp_epilogue_t epilogue,
+                                                  const float *fisher_n, float threshold_y, float scale_y,
+                                                  void *packed_Y, size_t packed_Y_bytes, float *scores_y,
+                                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Offline weight quantization with sensitivity-weighted clipping (Sec. 3.3, Eq. 11): the E4M3

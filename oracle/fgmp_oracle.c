@@ -397,6 +397,62 @@ int fgmp_oracle_gemm(const double *ax, double Sx, const double *aw, double Sw,
 }
 
 /* ------------------------------------------------------------------ */
+/* Gated activation in front of the output quantizer                   */
+/* ------------------------------------------------------------------ */
+
+/* The paper's unit quantizes a layer's results before they are written out
+ * [Sec. 4.2]; between the two MLP products of the Llama models it evaluates
+ * sits h = SiLU(g) * u with SiLU(g) = g / (1 + e^-g), which the paper does
+ * not discuss.  Because the quantized codes depend on h to the last bit, h is
+ * defined here as a fixed sequence of separately rounded fp32 operations:
+ *
+ *   E(x), x clamped to [-87, 88]:
+ *     n = nearest integer to fl(x * fl(log2 e)), ties to even
+ *     r = fl(fl(x - n * C1) - fl(n * C2)),  C1 = 0.693359375 (n * C1 is exact),
+ *                                           C2 = fl(ln 2 - C1)
+ *     p = the degree-7 Taylor polynomial of e^r by Horner's rule, every
+ *         multiply and every add rounded to fp32, coefficients fl(1/k!)
+ *     E = p * 2^n (exact)
+ *   h = fl(fl(g / fl(1 + E(-g))) * u)
+ *
+ * |r| <= 0.347, so the polynomial's truncation error is below 2^-27; the
+ * pins compare E and h with the fp64 functions (a few units in the last
+ * place) and check the closed forms at 0 and for large |g|. */
+static float exp_fp32_steps(float x)
+{
+    if (x > 88.0f) x = 88.0f;
+    if (x < -87.0f) x = -87.0f;
+    const float y = x * 1.44269504f;
+    const float n = rintf(y); /* round-to-nearest-even is the default mode */
+    float r = x - n * 0.693359375f;
+    r = r - n * -2.12194440e-4f;
+    static const float inv_fact[8] = {1.0f, 1.0f, 0.5f, 1.0f / 6.0f, 1.0f / 24.0f,
+                                      1.0f / 120.0f, 1.0f / 720.0f, 1.0f / 5040.0f};
+    float p = inv_fact[7];
+    for (int k = 6; k >= 0; --k) {
+        const float pr = p * r;
+        p = pr + inv_fact[k];
+    }
+    union { uint32_t u; float f; } two_n;
+    two_n.u = (uint32_t)((int)n + 127) << 23;
+    return p * two_n.f;
+}
+
+float fgmp_oracle_exp_steps(float x) { return exp_fp32_steps(x); }
+
+/* h[i] = SiLU(g[i]) * u[i] as defined above. */
+void fgmp_oracle_silu_mul(const float *g, const float *u, int64_t n, float *h)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float e = exp_fp32_steps(-g[i]);
+        const float d = 1.0f + e;
+        const float s = g[i] / d;
+        h[i] = s * u[i];
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Threshold for a target fraction of high-precision blocks [Eq. 9]    */
 /* ------------------------------------------------------------------ */
 

@@ -67,6 +67,10 @@ def _load():
     lib.fgmp_oracle_gemm.restype = ctypes.c_int
     lib.fgmp_oracle_gemm.argtypes = [f64p, ctypes.c_double, f64p, ctypes.c_double, i64,
                                      i64p, i64, i64p, i64, f64p, f64p]
+    lib.fgmp_oracle_exp_steps.restype = ctypes.c_float
+    lib.fgmp_oracle_exp_steps.argtypes = [ctypes.c_float]
+    lib.fgmp_oracle_silu_mul.restype = None
+    lib.fgmp_oracle_silu_mul.argtypes = [f32p, f32p, i64, f32p]
     lib.fgmp_oracle_threshold.restype = ctypes.c_float
     lib.fgmp_oracle_threshold.argtypes = [f32p, i64, ctypes.c_double]
     lib.fgmp_oracle_storage_bits.restype = i64
@@ -188,6 +192,32 @@ def gemm(ax: np.ndarray, sx: float, aw: np.ndarray, sw: float, rows=None, cols=N
     if rc != 0:
         raise ValueError("fgmp_oracle_gemm: bad argument")
     return Y, tol
+
+
+def exp_steps(x: float) -> float:
+    """The fp32 exponential the gated activation is defined with (see the C source)."""
+    return float(_load().fgmp_oracle_exp_steps(float(np.float32(x))))
+
+
+def silu_mul(g: np.ndarray, u: np.ndarray) -> np.ndarray:
+    """h = SiLU(g) * u, elementwise, in the fixed fp32 sequence of the C source."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    if g.shape != u.shape:
+        raise ValueError("silu_mul: shapes differ")
+    h = np.empty_like(g)
+    _load().fgmp_oracle_silu_mul(_ptr(g, ctypes.c_float), _ptr(u, ctypes.c_float), g.size, _ptr(h, ctypes.c_float))
+    return h
+
+
+def gate_columns(y: np.ndarray) -> np.ndarray:
+    """The gated activation over a product whose columns come in groups of 64: columns 64q .. 64q+31 are
+    the gate values of hidden units 32q .. 32q+31, columns 64q+32 .. 64q+63 their up values."""
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    if y.ndim != 2 or y.shape[1] % 64 != 0:
+        raise ValueError("gate_columns: the column count must be a multiple of 64")
+    v = y.reshape(y.shape[0], y.shape[1] // 64, 2, 32)
+    return silu_mul(v[:, :, 0, :], v[:, :, 1, :]).reshape(y.shape[0], y.shape[1] // 2)
 
 
 def threshold(scores: np.ndarray, fraction: float) -> float:

@@ -104,6 +104,26 @@ fgmp_status_t fgmp_quant_gemm_fused_packed_out(const void *X, fgmp_dtype_t dt, i
                                  as_stream(stream));
 }
 
+size_t fgmp_workspace_bytes_packed_out_ex(int64_t M, int64_t N, int64_t K, fgmp_epilogue_t epilogue)
+{
+    if (epilogue != FGMP_EPILOGUE_NONE && epilogue != FGMP_EPILOGUE_SILU_GATE) return 0;
+    const int64_t n_unit = epilogue == FGMP_EPILOGUE_SILU_GATE ? 64 : kBlock;
+    if (M <= 0 || N <= 0 || K <= 0 || K % kBlock != 0 || N % n_unit != 0) return 0;
+    return gemm_workspace_bytes_packed_out(M, N, K, (int)epilogue);
+}
+
+fgmp_status_t fgmp_quant_gemm_fused_packed_out_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                                  const float *fisher_k, float threshold, float scale_x,
+                                                  const void *packed_W, int64_t N, fgmp_epilogue_t epilogue,
+                                                  const float *fisher_n, float threshold_y, float scale_y,
+                                                  void *packed_Y, size_t packed_Y_bytes, float *scores_y,
+                                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    return quant_gemm_packed_out(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, fisher_n, threshold_y,
+                                 scale_y, packed_Y, packed_Y_bytes, scores_y, workspace, workspace_bytes,
+                                 as_stream(stream), (int)epilogue);
+}
+
 fgmp_status_t fgmp_quantize_weights_clip(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,
                                          const float *fisher, int64_t ld_fisher, float threshold,
                                          float tensor_scale, void *packed_W, size_t packed_bytes,

@@ -15,6 +15,7 @@
 
 #include <algorithm>
 
+#include "fgmp_elementwise.hpp"
 #include "fgmp_gemm_common.hpp"
 
 namespace fgmp {
@@ -370,27 +371,45 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
 // Fused call whose results are quantized and packed instead of stored as FP32 (Sec. 4.2).  Prefill
 // shapes do it in the GEMM's epilogue; other shapes (and the two-pass path) write FP32 results to the
 // workspace and run the standalone quantizer over them -- the same arithmetic on the same values.
-size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K)
+size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K, int epilogue)
 {
-    return (size_t)align_up(gemm_workspace_bytes(M, N, K), 256) + (size_t)align_up((uint64_t)M * N * 4, 256);
+    // FP32 staging of the product for the shapes whose epilogue cannot quantize, and of the gated values
+    const size_t staged = (size_t)align_up((uint64_t)M * N * 4, 256);
+    const size_t gated = epilogue == FGMP_EPILOGUE_SILU_GATE ? (size_t)align_up((uint64_t)M * (N / 2) * 4, 256) : 0;
+    return (size_t)align_up(gemm_workspace_bytes(M, N, K), 256) + staged + gated;
+}
+
+// h[m][32 q + c] = SiLU(y[m][64 q + c]) * y[m][64 q + 32 + c]: the gated activation over a staged product
+// (the shapes whose GEMM epilogue cannot apply it)
+__global__ __launch_bounds__(256) void silu_gate_kernel(const float *__restrict__ y, int64_t ldy, int64_t M,
+                                                         int64_t n_out, float *__restrict__ h)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * n_out) return;
+    const int64_t m = i / n_out, c = i % n_out;
+    const float *row = y + m * ldy + (c / 32) * kGateGroup + (c % 32);
+    h[i] = silu_mul(row[0], row[32]);
 }
 
 fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
                                     const float *fisher_k, float threshold, float scale_x, const void *packed_W,
                                     int64_t N, const float *fisher_n, float threshold_y, float scale_y,
                                     void *packed_Y, size_t packed_Y_bytes, float *scores_y, void *workspace,
-                                    size_t workspace_bytes, hipStream_t st)
+                                    size_t workspace_bytes, hipStream_t st, int epilogue)
 {
     if (!fisher_n || !packed_Y || !workspace) return FGMP_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (epilogue != FGMP_EPILOGUE_NONE && epilogue != FGMP_EPILOGUE_SILU_GATE) return FGMP_ERR_INVALID_ARG;
     if (!(scale_y > 0.0f) || !(scale_y < INFINITY) || threshold_y != threshold_y) return FGMP_ERR_INVALID_ARG;
-    if (N % kBlock != 0 || K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    const bool gate = epilogue == FGMP_EPILOGUE_SILU_GATE;
+    if (N % (gate ? kGateGroup : kBlock) != 0 || K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    const int64_t n_out = gate ? N / 2 : N;   // columns of the quantized result
     if (((uintptr_t)fisher_n | (uintptr_t)packed_Y | (uintptr_t)scores_y | (uintptr_t)workspace) % 16 != 0)
         return FGMP_ERR_BAD_ALIGN;
     if (M * (N / kBlock) >= (int64_t)1 << 32) return FGMP_ERR_UNSUPPORTED;
-    const PackedLayout ly = make_layout(M, N);
+    const PackedLayout ly = make_layout(M, n_out);
     if (packed_Y_bytes < ly.total_bytes) return FGMP_ERR_BUFFER_TOO_SMALL;
-    if (workspace_bytes < gemm_workspace_bytes_packed_out(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
+    if (workspace_bytes < gemm_workspace_bytes_packed_out(M, N, K, epilogue)) return FGMP_ERR_BUFFER_TOO_SMALL;
     PackOut po;
     po.out = make_view(packed_Y, ly);
     po.layout = ly;
@@ -398,6 +417,7 @@ fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, i
     po.T = threshold_y;
     po.S = scale_y;
     po.scores = scores_y;
+    po.gate = gate ? 1 : 0;
     const size_t base_bytes = gemm_workspace_bytes(M, N, K);
     fgmp_status_t rc = quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, nullptr, N, workspace,
                                   base_bytes, st, FGMP_SCORE_NVFP4_ERROR, &po);
@@ -406,7 +426,14 @@ fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, i
     rc = quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Yf, N, workspace, base_bytes, st,
                     FGMP_SCORE_NVFP4_ERROR, nullptr);
     if (rc != FGMP_OK) return rc;
-    return quantize_tensor(Yf, FGMP_F32, M, N, N, fisher_n, 0, threshold_y, scale_y, packed_Y, packed_Y_bytes,
+    if (gate) {
+        float *Hf = Yf + align_up((uint64_t)M * N * 4, 256) / 4;
+        const int64_t n = M * n_out;
+        hipLaunchKernelGGL(silu_gate_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, Yf, N, M, n_out, Hf);
+        if (hipGetLastError() != hipSuccess) return FGMP_ERR_HIP;
+        Yf = Hf;
+    }
+    return quantize_tensor(Yf, FGMP_F32, M, n_out, n_out, fisher_n, 0, threshold_y, scale_y, packed_Y, packed_Y_bytes,
                            scores_y, /*compact=*/false, st);
 }
 

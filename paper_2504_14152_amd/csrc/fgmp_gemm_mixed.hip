@@ -31,6 +31,7 @@
 // through the workspace after their loops (see SplitTail).
 #include <type_traits>
 
+#include "fgmp_elementwise.hpp"
 #include "fgmp_gemm_common.hpp"
 #include "fgmp_quant_block.hpp"
 
@@ -87,8 +88,10 @@ template <int kPending, int kBPT> __device__ __forceinline__ void wait_loaded(u3
 
 // kPackOut: instead of storing FP32 results, the epilogue scores and quantizes them block by block (16
 // consecutive output columns) and writes a packed tensor -- the placement of the quantization unit in
-// the paper (Sec. 4.2): results are quantized before they leave for memory.
-template <int kWM, int kWN, bool kPackOut>
+// the paper (Sec. 4.2): results are quantized before they leave for memory.  kGate (with kPackOut): the
+// weight rows come in groups of 32 gate rows and 32 up rows, and what is quantized is
+// SiLU(gate result) * up result, half as many columns.
+template <int kWM, int kWN, bool kPackOut, bool kGate>
 __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Float16 *__restrict__ A, int64_t ld,
                                                                        PackedView W, PackedLayout lw, int nk_total,
                                                                        float *__restrict__ Y, int64_t ldy, int64_t M,
@@ -419,13 +422,22 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         const PackedLayout &ly = po.layout;
         const float inv_Sy = 1.0f / po.S, S6y = 6.0f * po.S;
         const int brow = lane & 31, bblk = lane >> 5;
+        // gated: a wave's two accumulator tiles of a row band are the gate and the up values of the same 32
+        // hidden units, element by element; the workgroup's 256 weight rows give 128 output columns
+        static_assert(!kGate || TN == 2, "a wave must hold one group of 32 gate and 32 up rows");
+        constexpr int kOutTiles = kGate ? 1 : TN, kOutBN = kGate ? kBN / 2 : kBN;
+        const int64_t n_out = kGate ? N / 2 : N;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
+            for (int j = 0; j < kOutTiles; ++j) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    tbuf[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kTStride + (lane & 31)] = acc[i][j][r] * ss;
+                for (int r = 0; r < 16; ++r) {
+                    float v;
+                    if constexpr (kGate) v = silu_mul(acc[i][0][r] * ss, acc[i][1][r] * ss);
+                    else v = acc[i][j][r] * ss;
+                    tbuf[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kTStride + (lane & 31)] = v;
+                }
                 float x[16], f[16];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
@@ -433,9 +445,9 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
                     x[4 * v] = t4.x; x[4 * v + 1] = t4.y; x[4 * v + 2] = t4.z; x[4 * v + 3] = t4.w;
                 }
                 const int row_l = wm * (TM * 32) + i * 32 + brow;              // within the workgroup's 256 x 256
-                const int col_l = wn * (TN * 32) + j * 32 + 16 * bblk;
-                const int64_t row = tm * kBM + row_l, col0 = tn * kBN + col_l;
-                const bool valid = row < M && col0 < N;
+                const int col_l = wn * (kOutTiles * 32) + j * 32 + 16 * bblk;   // within the workgroup's output columns
+                const int64_t row = tm * kBM + row_l, col0 = tn * kOutBN + col_l;
+                const bool valid = row < M && col0 < n_out;
                 if (valid) load16(po.fisher + col0, f);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
@@ -470,8 +482,8 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
             }
         __syncthreads();
         if (tid < 64) {
-            const int64_t rt = tm * (kBM / kTileRows) + (tid >> 1), kt = tn * (kBN / kTileK) + (tid & 1);
-            if (rt < ly.n_rt && kt < ly.n_kt) {
+            const int64_t rt = tm * (kBM / kTileRows) + (tid >> 1), kt = tn * (kOutBN / kTileK) + (tid & 1);
+            if (rt < ly.n_rt && kt < ly.n_kt && (tid & 1) < kOutBN / kTileK) {
                 const int64_t tile = rt * ly.n_kt + kt;
                 po.out.M[tile] = m_lds[tid];
                 po.out.T[tile] = (uint32_t)(tile * kTileSlots);
@@ -539,12 +551,16 @@ void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, con
 #define FGMP_MIXED_WN 4
 #endif
     constexpr int kThreads = FGMP_MIXED_WM * FGMP_MIXED_WN * 64;
-    if (pack_out != nullptr)
-        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, true>), dim3(grid),
+    if (pack_out != nullptr && pack_out->gate)
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, true, true>), dim3(grid),
+                           dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
+                           *pack_out, sp);
+    else if (pack_out != nullptr)
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, true, false>), dim3(grid),
                            dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
                            *pack_out, sp);
     else
-        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false>), dim3(grid),
+        hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false, false>), dim3(grid),
                            dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
                            PackOut{}, sp);
     if (g_ev_stop) (void)hipEventRecord(g_ev_stop, st);

@@ -35,12 +35,12 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
                          float threshold, float scale_x, const void *packed_W, int64_t N, float *Y, int64_t ldy,
                          void *workspace, size_t workspace_bytes, hipStream_t st,
                          int score_mode = FGMP_SCORE_NVFP4_ERROR, const PackOut *pack_out = nullptr);
-size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K);
+size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K, int epilogue = FGMP_EPILOGUE_NONE);
 fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
                                     const float *fisher_k, float threshold, float scale_x, const void *packed_W,
                                     int64_t N, const float *fisher_n, float threshold_y, float scale_y,
                                     void *packed_Y, size_t packed_Y_bytes, float *scores_y, void *workspace,
-                                    size_t workspace_bytes, hipStream_t st);
+                                    size_t workspace_bytes, hipStream_t st, int epilogue = FGMP_EPILOGUE_NONE);
 // Decode shapes (few rows of X): weight-streaming kernel.  X is given as FP16 values (`x16`,
 // gemm_skinny_x16_rows(M) rows of ld16 halves; rows from M rounded up to 8 on are never used for a
 // stored output) plus the header of its packed form.
@@ -75,6 +75,7 @@ struct PackOut {
     const float *fisher;   // N sensitivities (input channels of the next layer)
     float T, S;            // threshold and tensor scale of the output tensor
     float *scores;         // nullable, M * N / 16
+    int gate;              // nonzero: quantize SiLU(gate) * up of the 32 + 32 row groups of W; `out` is M x N / 2
 };
 // The last, partly filled round of tiles of the prefill kernel, split in two along K (n_split 0: no split).
 struct SplitTail {

@@ -61,6 +61,11 @@ def lib() -> ctypes.CDLL:
     L.fgmp_quantize_weights_clip.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i64, f32, f32, vp, sz, vp, vp, sz, vp]
     L.fgmp_workspace_bytes_packed_out.restype = sz
     L.fgmp_workspace_bytes_packed_out.argtypes = [i64, i64, i64]
+    L.fgmp_workspace_bytes_packed_out_ex.restype = sz
+    L.fgmp_workspace_bytes_packed_out_ex.argtypes = [i64, i64, i64, ctypes.c_int]
+    L.fgmp_quant_gemm_fused_packed_out_ex.restype = ctypes.c_int
+    L.fgmp_quant_gemm_fused_packed_out_ex.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, ctypes.c_int,
+                                                      vp, f32, f32, vp, sz, vp, vp, sz, vp]
     L.fgmp_quant_gemm_fused_packed_out.restype = ctypes.c_int
     L.fgmp_quant_gemm_fused_packed_out.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, vp, f32, f32,
                                                    vp, sz, vp, vp, sz, vp]
@@ -149,6 +154,7 @@ def _alloc_packed(rows: int, K: int, device) -> Packed:
 
 
 SCORE_MODES = {"nvfp4_error": 0, "delta": 1}   # fgmp_score_mode_t
+EPILOGUE_NONE, EPILOGUE_SILU_GATE = 0, 1          # fgmp_epilogue_t
 
 
 def quantize_weights(W: torch.Tensor, fisher: torch.Tensor, threshold: float, tensor_scale: float,
@@ -244,22 +250,35 @@ def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, 
 def quant_gemm_fused_packed_out(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, scale_x: float,
                                 pW: Packed, fisher_n: torch.Tensor, threshold_y: float, scale_y: float,
                                 want_scores: bool = False, out: Packed | None = None,
-                                workspace: torch.Tensor | None = None):
-    """Fused step whose results are quantized and packed (a packed M x N activation tensor)."""
+                                workspace: torch.Tensor | None = None, epilogue: int | None = None):
+    """Fused step whose results are quantized and packed (a packed M x N activation tensor; with
+    epilogue=EPILOGUE_SILU_GATE the gated activation of the 32 + 32 row groups of W, M x N/2)."""
     _require_cuda(X, fisher_k, fisher_n)
     M, K = X.shape
     if K != pW.K:
         raise FgmpError("K mismatch")
     N = pW.rows
-    out = out or _alloc_packed(M, N, X.device)
-    scores = torch.empty((M, N // 16), dtype=torch.float32, device=X.device) if want_scores else None
-    if workspace is None:
-        workspace = torch.empty(int(lib().fgmp_workspace_bytes_packed_out(M, N, K)), dtype=torch.uint8, device=X.device)
-    rc = lib().fgmp_quant_gemm_fused_packed_out(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
-                                                float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(fisher_n),
-                                                float(threshold_y), float(scale_y), _ptr(out.buf), out.buf.numel(),
-                                                _ptr(scores), _ptr(workspace), workspace.numel(), _stream())
-    _check(rc, "fgmp_quant_gemm_fused_packed_out")
+    n_out = N // 2 if epilogue == EPILOGUE_SILU_GATE else N
+    out = out or _alloc_packed(M, n_out, X.device)
+    scores = torch.empty((M, n_out // 16), dtype=torch.float32, device=X.device) if want_scores else None
+    if epilogue is None:
+        if workspace is None:
+            workspace = torch.empty(int(lib().fgmp_workspace_bytes_packed_out(M, N, K)), dtype=torch.uint8, device=X.device)
+        rc = lib().fgmp_quant_gemm_fused_packed_out(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                                    float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(fisher_n),
+                                                    float(threshold_y), float(scale_y), _ptr(out.buf), out.buf.numel(),
+                                                    _ptr(scores), _ptr(workspace), workspace.numel(), _stream())
+        _check(rc, "fgmp_quant_gemm_fused_packed_out")
+    else:
+        if workspace is None:
+            workspace = torch.empty(int(lib().fgmp_workspace_bytes_packed_out_ex(M, N, K, int(epilogue))),
+                                    dtype=torch.uint8, device=X.device)
+        rc = lib().fgmp_quant_gemm_fused_packed_out_ex(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                                       float(threshold), float(scale_x), _ptr(pW.buf), N, int(epilogue),
+                                                       _ptr(fisher_n), float(threshold_y), float(scale_y), _ptr(out.buf),
+                                                       out.buf.numel(), _ptr(scores), _ptr(workspace), workspace.numel(),
+                                                       _stream())
+        _check(rc, "fgmp_quant_gemm_fused_packed_out_ex")
     return (out, scores) if want_scores else out
 
 

@@ -54,6 +54,15 @@ def test_sizes_and_host_side_argument_checks():
     assert L.fgmp_quantize_weights_clip(256, 0, 8, 128, 128, 256, 0, 0.0, 1.0, 256, 1 << 20, None, 256, 63, None) == -4
     assert fgmp.lib().fgmp_workspace_bytes_packed_out(4096, 12288, 4096) >= fgmp.workspace_bytes(4096, 12288, 4096) + 4096 * 12288 * 4
     assert fgmp.lib().fgmp_workspace_bytes_packed_out(64, 24, 128) == 0          # N must be a multiple of 16
+    # gated epilogue: groups of 64 weight rows, a second staging area for the gated values, known operators only
+    wb = fgmp.lib().fgmp_workspace_bytes_packed_out_ex
+    assert wb(64, 96, 128, 1) == 0 and wb(64, 128, 128, 7) == 0
+    assert wb(64, 128, 128, 0) == fgmp.lib().fgmp_workspace_bytes_packed_out(64, 128, 128)
+    assert wb(64, 128, 128, 1) >= wb(64, 128, 128, 0) + 64 * 64 * 4
+    assert L.fgmp_quant_gemm_fused_packed_out_ex(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 96, 1, 256, 0.0, 1.0, 256, 1 << 20,
+                                                 None, 256, 1 << 30, None) == -2
+    assert L.fgmp_quant_gemm_fused_packed_out_ex(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 128, 5, 256, 0.0, 1.0, 256, 1 << 20,
+                                                 None, 256, 1 << 30, None) == -1
     assert L.fgmp_quant_gemm_fused_packed_out(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 24, 256, 0.0, 1.0, 256, 1 << 20,
                                               None, 256, 1 << 20, None) == -2
     assert L.fgmp_quant_gemm_fused_packed_out(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 32, 256, 0.0, 0.0, 256, 1 << 20,

@@ -433,6 +433,62 @@ def test_packed_output_on_random_inputs_is_consistent(M, K, N):
     assert fgmp.packed_info(got)["n_fp8_blocks"] == int(0.2 * M * N / 16 + 0.5)
 
 
+@pytest.mark.parametrize("M,K,N", [(136, 128, 256), (300, 64, 512), (257, 128, 64), (24, 128, 128)])
+def test_fused_gated_packed_output_matches_oracle(M, K, N):
+    """The same with the gated activation in front of the quantizer: what is scored, quantized and packed
+    is SiLU(gate) * up of the 32 + 32 row groups of W, as the oracle computes it from its own product
+    (M > 32: in the GEMM epilogue; M = 24: staged through FP32)."""
+    _say(f"gated packed output M={M} K={K} N={N}")
+    x, w, ones, y32 = _exact_product_case(M, K, N, 37)
+    h32 = orc.gate_columns(y32)
+    f_h = synth.fisher_per_channel(N // 2, 37, 3)
+    s_h = float(np.float32(np.abs(h32).max()) / np.float32(448.0))
+    T_h = orc.threshold(orc.quantize(h32, f_h, np.inf, s_h)["scores"], 0.2)
+    want = orc.quantize(h32, f_h, T_h, s_h)
+    xd, wd, od = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV), torch.from_numpy(ones).to(DEV)
+    pW = fgmp.quantize_weights(wd, od, 0.0, 1.0)
+    pH, scores = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_h).to(DEV), T_h, s_h,
+                                                  want_scores=True, epilogue=fgmp.EPILOGUE_SILU_GATE)
+    _assert_quant_equal(pH, scores, want, "gated packed output")
+    info = fgmp.packed_info(pH)
+    assert info["rows"] == M and info["K"] == N // 2 and info["n_fp8_blocks"] == int(want["mask"].sum())
+    # FC2 consumes it
+    w2 = synth.weights(40, N // 2, 37, 4)
+    w2d, w2ref = _to_dev_bf16(w2)
+    f2 = synth.fisher_per_channel(N // 2, 37, 5)
+    s2 = float(synth.default_tensor_scale(w2ref))
+    pW2 = fgmp.quantize_weights(w2d, torch.from_numpy(f2).to(DEV), np.inf, s2)
+    Z = fgmp.gemm(pH, pW2)
+    q2 = orc.quantize(w2ref, f2, np.inf, s2)
+    zw, tol = orc.gemm(orc.dequantize(want["codes"], want["scales"], want["mask"]), s_h,
+                       orc.dequantize(q2["codes"], q2["scales"], q2["mask"]), s2)
+    assert np.all(np.abs(Z.cpu().numpy().astype(np.float64) - zw) <= tol)
+    # the operator none is the plain packed-output call
+    f_n = torch.from_numpy(synth.fisher_per_channel(N, 37, 6)).to(DEV)
+    a = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, f_n, 1.0, 2.0)
+    b = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, f_n, 1.0, 2.0, epilogue=fgmp.EPILOGUE_NONE)
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(a), fgmp.unpack_canonical(b)))
+
+
+@pytest.mark.parametrize("M,K,N", [(200, 512, 320), (4352, 256, 4096), (9, 1024, 192)])
+def test_gated_packed_output_on_random_inputs_is_consistent(M, K, N):
+    """On ordinary inputs: the gated epilogue equals the oracle's gate applied to the very FP32 results
+    the plain fused call writes, then the standalone quantizer -- so the kernel's SiLU is the oracle's,
+    bit for bit, on realistic values (whole and split tiles in the second shape, the staged path in the third)."""
+    c = _quantized_pair(M, K, N, 41, 0.1, per_elem_w=False)
+    Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    h = torch.from_numpy(orc.gate_columns(Y.cpu().numpy())).to(DEV)
+    f_h = torch.from_numpy(synth.fisher_per_channel(N // 2, 41, 9)).to(DEV)
+    s_h = float(h.abs().max()) / 448.0
+    _, sc0 = fgmp.quantize_activations(h, f_h, np.inf, s_h, want_scores=True)
+    T_h = fgmp.threshold_for_fraction(sc0, 0.15)
+    ref, sc_ref = fgmp.quantize_activations(h, f_h, T_h, s_h, want_scores=True)
+    got, sc_got = fgmp.quant_gemm_fused_packed_out(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], f_h, T_h, s_h,
+                                                   want_scores=True, epilogue=fgmp.EPILOGUE_SILU_GATE)
+    assert torch.equal(sc_ref, sc_got)
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(ref), fgmp.unpack_canonical(got)))
+
+
 def test_quantize_is_deterministic():
     x = synth.activations(512, 2048, 9, 51)
     xd, xref = _to_dev_bf16(x)

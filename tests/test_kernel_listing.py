@@ -23,8 +23,9 @@ from paper_2504_14152_amd import build
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 SRC = os.path.join(build.CSRC, "fgmp_gemm_mixed.hip")
 KERNELS = {
-    "fp32 output": "_ZN4fgmp17gemm_mixed_kernelILi2ELi4ELb0EE",
-    "packed output": "_ZN4fgmp17gemm_mixed_kernelILi2ELi4ELb1EE",
+    "fp32 output": "_ZN4fgmp17gemm_mixed_kernelILi2ELi4ELb0ELb0EE",
+    "packed output": "_ZN4fgmp17gemm_mixed_kernelILi2ELi4ELb1ELb0EE",
+    "gated packed output": "_ZN4fgmp17gemm_mixed_kernelILi2ELi4ELb1ELb1EE",
 }
 
 pytestmark = pytest.mark.skipif(shutil.which(HIPCC) is None and not os.path.exists(HIPCC), reason="hipcc not available")

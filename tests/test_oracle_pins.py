@@ -482,6 +482,65 @@ def test_gemm_row_and_column_sampling():
 
 # ---------------------------------------------------------------- closed forms the paper prints
 
+# ------------------------------------------------------------------ gated activation in front of the output quantizer
+
+def _ulps(got, want64):
+    want32 = np.asarray(want64, dtype=np.float64).astype(np.float32)
+    return np.abs(np.asarray(got, dtype=np.float64) - want64) / np.maximum(np.spacing(np.abs(want32)).astype(np.float64), 1e-45)
+
+
+def test_exponential_steps_against_fp64():
+    """The fp32 exponential the gate is defined with: within 1.5 ulp of exp() over its whole range, exact at
+    0, clamped outside [-87, 88], never decreasing."""
+    x = np.concatenate([np.linspace(-87.0, 88.0, 30001), np.linspace(-1.0, 1.0, 4001)]).astype(np.float32)
+    e = np.array([orc.exp_steps(float(v)) for v in x], dtype=np.float64)
+    assert _ulps(e, np.exp(x.astype(np.float64))).max() <= 1.5
+    assert orc.exp_steps(0.0) == 1.0 and orc.exp_steps(-0.0) == 1.0
+    assert orc.exp_steps(1000.0) == orc.exp_steps(88.0) and orc.exp_steps(-1000.0) == orc.exp_steps(-87.0)
+    xs = np.sort(x)
+    es = np.array([orc.exp_steps(float(v)) for v in xs])
+    assert np.all(np.diff(es) >= 0)
+
+
+def test_silu_mul_against_fp64_definition():
+    """h = g / (1 + e^-g) * u: a few ulp from the fp64 value; closed forms at 0 and where e^-g vanishes
+    beside 1; SiLU(g) - SiLU(-g) = g; the sign of u carries over."""
+    rng = np.random.default_rng(5)
+    g = np.concatenate([rng.normal(0, 3, 40000), rng.uniform(-30, 30, 10000), rng.normal(0, 0.05, 5000)]).astype(np.float32)
+    u = rng.normal(0, 2, g.size).astype(np.float32)
+    h = orc.silu_mul(g, u)
+    g64, u64 = g.astype(np.float64), u.astype(np.float64)
+    assert _ulps(h, g64 / (1.0 + np.exp(-g64)) * u64).max() <= 4.0
+    # g = 0 (either sign) gives a zero; 1 + e^-g is 1 from g = 17 on, so h is the rounded product g u
+    assert np.array_equal(orc.silu_mul(np.array([0.0, -0.0], np.float32), np.array([3.0, 3.0], np.float32)), [0.0, -0.0])
+    big = np.array([17.0, 20.5, 88.0, 300.0], np.float32)
+    assert np.array_equal(orc.silu_mul(big, np.full(4, 1.25, np.float32)), big * np.float32(1.25))
+    # far below zero SiLU(g) = g e^g vanishes; the clamp at 87 keeps the result a tiny negative number
+    tiny = orc.silu_mul(np.array([-50.0, -100.0], np.float32), np.ones(2, np.float32))
+    assert np.all(tiny <= 0) and np.all(np.abs(tiny) < 1e-19)
+    # odd-part identity, from the same routine with u = 1
+    gp = np.abs(g[:20000])
+    one = np.ones_like(gp)
+    diff = orc.silu_mul(gp, one).astype(np.float64) - orc.silu_mul(-gp, one).astype(np.float64)
+    assert np.all(np.abs(diff - gp) <= 3 * np.spacing(gp))
+    assert np.array_equal(orc.silu_mul(g, -u), -h)
+
+
+def test_gate_columns_pairs_rows_of_a_group_of_64():
+    """Columns 64q + c and 64q + 32 + c (c < 32) of the product are the gate and up values of hidden unit 32q + c."""
+    rng = np.random.default_rng(6)
+    y = rng.normal(0, 2, (5, 192)).astype(np.float32)
+    h = orc.gate_columns(y)
+    assert h.shape == (5, 96)
+    for m in range(5):
+        for j in (0, 1, 31, 32, 63, 64, 95):
+            q, c = divmod(j, 32)
+            want = orc.silu_mul(y[m:m + 1, 64 * q + c], y[m:m + 1, 64 * q + 32 + c])[0]
+            assert h[m, j] == want
+    with pytest.raises(ValueError):
+        orc.gate_columns(y[:, :96])
+
+
 def test_storage_accounting_reproduces_printed_memory_savings():
     J = 1000000
     for frac_fp4, key in ((0.7, "mem_saving_70pct_fp4"), (0.9, "mem_saving_90pct_fp4")):
