@@ -27,6 +27,8 @@
  *             scale multiplies only where an FP4 operand is involved
  *                                                                [Sec. 4.1]
  *   threshold order statistic of the scores of one tensor        [Eq. 9]
+ *   gate      h = SiLU(g) * u in front of the output quantizer; not in the
+ *             paper, defined further down as a fixed fp32 sequence
  *
  * Readings the paper leaves open (one FP32 scale S per tensor, RNE for the
  * block scale, one reciprocal per block, balanced summation tree, zero block
@@ -38,7 +40,8 @@
  * scaling invariants and an fp64 recomputation, the threshold by its counting
  * property, the product by numpy fp64 brute force and its two single-format
  * special cases, the byte accounting by the memory savings the paper prints
- * (Sec. 5.4.1).  End-to-end model quality (perplexity etc.) is "parity
+ * (Sec. 5.4.1), the gated activation and its exponential by the fp64
+ * functions (units in the last place) and their closed forms.  End-to-end model quality (perplexity etc.) is "parity
  * unpinned": the paper prints no worked example of a quantized block.
  */
 #include <math.h>
