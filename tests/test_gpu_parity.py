@@ -772,3 +772,35 @@ def test_gemm_kernel_timing_hook():
     torch.cuda.synchronize()
     assert ea.elapsed_time(eb) == ms
 
+
+@pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (300, 512, 520)])
+def test_fused_call_replays_in_a_hip_graph(M, K, N):
+    """The hot-path calls only enqueue kernels on the caller's stream (no allocation, no synchronization,
+    no memset nodes: arrival counters are cleared by the kernel that prepares the activations), so a
+    captured step can be replayed: a decode shape (split-K counters) and a prefill shape whose tiles are
+    computed in two parts.  Every replay, with eager work and synchronizations in between, must
+    reproduce the eager result bit for bit."""
+    c = _quantized_pair(M, K, N, 43, 0.1, per_elem_w=False)
+    ws = torch.empty(fgmp.workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
+    Y_eager = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], workspace=ws).clone()
+    Y = torch.empty_like(Y_eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], out=Y, workspace=ws)   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], out=Y, workspace=ws)
+    for rep in range(4):
+        Y.zero_()
+        ws.fill_(0xA5 if rep & 1 else 0)          # whatever the workspace holds between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y_eager), f"replay {rep}"
+        # eager work of the program between replays
+        Z = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+        assert torch.equal(Z, Y_eager)
+
