@@ -399,11 +399,7 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int64_t row = tm * kBM + wm * (TM * 32) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-#ifdef FGMP_ABL_NOSTORE
-                    if (row < M && col < N && acc[i][j][r] == 12345.678f) Y[row * ldy + col] = acc[i][j][r] * ss;
-#else
                     if (row < M && col < N) Y[row * ldy + col] = acc[i][j][r] * ss;
-#endif
                 }
             }
     } else {
