@@ -96,13 +96,17 @@ struct SkinnyArgs {
 };
 
 // kWaves waves per workgroup, 16 weight rows each; they share the activations in LDS.
-template <int MT, int kWaves>
+// kXR: activation rows kept in LDS (8 when M <= 8, else all 16 MT): rows of the MFMA operand beyond them
+// alias the rows there are -- they only feed output rows that are never stored -- and the smaller
+// workgroup lets one more of them be resident per compute unit.
+template <int MT, int kWaves, int kXR>
 __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
 {
     constexpr int kRows = 16 * kWaves;   // weight rows per workgroup
     constexpr int kSkMaxCols = skinny_max_cols(MT), kSkHWin = skinny_h_window(MT);
     constexpr int kXRow = kSkMaxCols * kTileK + kSkXPad;
-    __shared__ __attribute__((aligned(1024))) _Float16 xs[16 * MT][kXRow];
+    static_assert(kXR == 16 * MT || (MT == 1 && kXR == 8), "rows of X in LDS");
+    __shared__ __attribute__((aligned(1024))) _Float16 xs[kXR][kXRow];
     // per wave (sel = which of its two row-tiles):
     __shared__ uint2 m_lds[kWaves][16];                       // mask words, [sel][K-tile]
     __shared__ uint32_t t_lds[kWaves][16];                    // plane-H offsets relative to the K range's first, [sel][K-tile]
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
     // still in flight).  Loads complete in issue order and these are the first, so every later wait
     // for a loaded register also covers them.
 #pragma unroll
-    for (int u = 0; u < 32 * MT / kWaves; ++u) {
+    for (int u = 0; u < 2 * kXR / kWaves; ++u) {
         const int id = wave + kWaves * u, r = id >> 1, h = id & 1;
         const int chunk = h * 64 + lane;
         const int src_chunk = chunk < ncols * (kTileK / 8) ? chunk : 0;
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(64 * kWaves) void gemm_skinny_kernel(SkinnyArgs a)
 #pragma unroll
     for (int i = 0; i < MT; ++i) acc[i] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    const _Float16 *xrow = &xs[nl][32 * g];
+    const _Float16 *xrow = &xs[nl % kXR][32 * g];
     auto consume = [&](int c, const SkinnyStage &st, uint32_t mbyte, uint32_t svc, uint32_t trel, uint2 up0, uint2 up1) {
         const uint32_t mbits = mbyte >> (2 * g);   // bits 0, 1: blocks 2g, 2g+1 are FP8
         const uint32_t s0 = svc & 0xFFu, s1 = svc >> 8;
@@ -459,8 +463,9 @@ fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const 
     a.counters = reinterpret_cast<uint32_t *>(ws + p.off_counters);
     a.Y = Y; a.ldy = ldy; a.M = M; a.N = N;
     const dim3 grid((unsigned)(p.row_groups * p.ksplit));
-    if (p.mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<2, 8>), grid, dim3(512), 0, st, a);
+    if (p.mt == 1 && M <= 8) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 8>), grid, dim3(256), 0, st, a);
+    else if (p.mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 16>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<2, 8, 32>), grid, dim3(512), 0, st, a);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }
 
