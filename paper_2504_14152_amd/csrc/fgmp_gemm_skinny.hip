@@ -37,8 +37,9 @@ namespace fgmp {
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 // K-tiles per workgroup and plane-H entries staged per row-tile and K range (FP8 blocks beyond fetch
-// their entry directly).  Sized by LDS: every workgroup of a launch should be resident at once (3 per
-// CU with 4 waves and up to 16 rows of X, 2 per CU with 8 waves and 17..32 rows).
+// their entry directly).  Sized by LDS: every workgroup of a launch should be resident at once (4 per
+// CU with 4 waves and up to 8 rows of X -- as many as the waves' 120 vector registers allow --, 3 with
+// 9..16 rows, 2 per CU with 8 waves and 17..32 rows).
 constexpr int skinny_max_cols(int mt) { return mt == 1 ? 8 : 7; }
 constexpr int skinny_h_window(int mt) { return mt == 1 ? 192 : 64; }
 constexpr int kSkPrefetch = 4;    // plane-L K-tiles in flight per wave (2..4 measure alike, 8 is slower)
