@@ -324,7 +324,8 @@ fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *
  * the caller synchronizes and reads hipEventElapsedTime.  Two null pointers
  * clear the hook; one null and one non-null pointer is FGMP_ERR_INVALID_ARG.
  * The pair is process-wide state, not synchronized: for single-threaded
- * measurement code only.
+ * measurement code only.  The events stay the caller's; clear the hook before
+ * destroying them.
  */
 fgmp_status_t fgmp_selftest_time_gemm_kernel(void *ev_start, void *ev_stop);
 
