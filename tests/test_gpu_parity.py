@@ -667,6 +667,51 @@ def test_gemm_llama_fc1_prefill_sampled():
     assert torch.equal(Yf, fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"]))
 
 
+def test_gemm_llama70b_fc1_shape_sampled():
+    """The sweep's shape (configs[4]: K 8192, N 57344, M 2048; 470 M weights, 1792 output tiles) and a
+    decode step on the same weights.  The weights are drawn on the device (seeded); the oracle quantizes
+    the sampled rows of X and W itself from the very same bf16 values."""
+    M, K, N, p = 2048, 8192, 57344, 0.1
+    _say("gemm 70B fc1 2048x8192x57344")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(70)
+    wd = torch.empty((N, K), dtype=torch.bfloat16, device=DEV).normal_(0.0, 0.02, generator=gen)
+    xd, xref = _to_dev_bf16(synth.activations(M, K, 70, 1))
+    fx, fw = synth.fisher_per_channel(K, 70, 3), synth.fisher_per_channel(K, 70, 4)
+    fxd, fwd = torch.from_numpy(fx).to(DEV), torch.from_numpy(fw).to(DEV)
+    sx, sw = float(synth.default_tensor_scale(xref)), float(wd.abs().max().float()) / 448.0
+    _, sxs = fgmp.quantize_activations(xd, fxd, np.inf, sx, want_scores=True)
+    _, sws = fgmp.quantize_weights(wd, fwd, np.inf, sw, want_scores=True)
+    Tx, Tw = fgmp.threshold_for_fraction(sxs, p), fgmp.threshold_for_fraction(sws, p)
+    del sxs, sws
+    pW = fgmp.quantize_weights(wd, fwd, Tw, sw)
+    info = fgmp.packed_info(pW)
+    assert info["n_fp8_blocks"] == int(p * info["n_blocks"] + 0.5)
+    rng = np.random.default_rng(170)
+    rows = np.sort(rng.choice(M, 24, replace=False))
+    cols = np.sort(np.concatenate([rng.choice(N, 300, replace=False), [0, N - 1]]))
+    cols = np.unique(cols)
+    wsel = wd[torch.from_numpy(cols).to(DEV)].float().cpu().numpy()
+    c = dict(xref=xref, wref=None, fx=fx, fw=fw, sx=sx, sw=sw, Tx=Tx, Tw=Tw)
+
+    def check(Y, xrows, label):
+        qx = orc.quantize(xref[xrows], fx, Tx, sx)
+        qw = orc.quantize(wsel, fw, Tw, sw)
+        want, tol = orc.gemm(orc.dequantize(qx["codes"], qx["scales"], qx["mask"]), sx,
+                             orc.dequantize(qw["codes"], qw["scales"], qw["mask"]), sw)
+        got = Y.cpu().numpy().astype(np.float64)[np.ix_(xrows, cols)]
+        err = np.abs(got - want)
+        _say(f"gemm {label}: max |err| / (1e-5 sum|xw|) = {float((err / np.maximum(tol, 1e-300)).max()):.4f}")
+        assert np.all(err <= tol), label
+    del wd
+    Y = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW)
+    check(Y, rows, "70B fc1 prefill sampled")
+    assert torch.isfinite(Y).all()
+    del Y
+    Yd = fgmp.quant_gemm_fused(xd[:8].contiguous(), fxd, Tx, sx, pW)
+    check(Yd, np.arange(8), "70B fc1 decode M=8")
+
+
 def test_gemm_fc2_shape_sampled():
     M, K, N = 512, 11008, 4096
     _say("gemm fc2 512x11008x4096")
