@@ -135,6 +135,39 @@ def test_quantize_activations_llama_qkv_full_size():
     _run_act_case(x, synth.fisher_per_channel(4096, 0, 3), 0.1, "qkv-prefill-X", bf16=True)
 
 
+def test_quantize_activations_standalone_size_sampled_rows():
+    """The standalone quantizer's benchmark tensor (16384 x 8192 bf16, 1% outlier channels, 8.4 M blocks),
+    drawn on the device; the oracle quantizes 96 whole rows (8-row tiles at the start, the end and in
+    between) from the same bf16 values and every field of those rows must agree."""
+    rows_n, K, p = 16384, 8192, 0.1
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(16)
+    x = torch.empty((rows_n, K), dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen)
+    ch = torch.randperm(K, device=DEV, generator=gen)[: K // 100]
+    x[:, ch] *= 20.0
+    xd = x.to(torch.bfloat16)
+    del x
+    f = synth.fisher_per_channel(K, 0, 16)
+    fd = torch.from_numpy(f).to(DEV)
+    S = float(xd.abs().max().float()) / 448.0
+    _, sc = fgmp.quantize_activations(xd, fd, np.inf, S, want_scores=True)
+    T = fgmp.threshold_for_fraction(sc, p)
+    del sc
+    pk, scores = fgmp.quantize_activations(xd, fd, T, S, want_scores=True)
+    info = fgmp.packed_info(pk)
+    assert info["n_fp8_blocks"] == int(p * info["n_blocks"] + 0.5)
+    rng = np.random.default_rng(16)
+    tiles = np.unique(np.concatenate([[0, rows_n // 8 - 1], rng.choice(rows_n // 8, 10, replace=False)]))
+    rows = np.concatenate([np.arange(8 * t, 8 * t + 8) for t in tiles])
+    ridx = torch.from_numpy(rows).to(DEV)
+    want = orc.quantize(xd[ridx].float().cpu().numpy(), f, T, S)
+    codes, scales, mask = fgmp.unpack_canonical(pk)
+    assert np.array_equal(mask[ridx].cpu().numpy(), want["mask"])
+    assert np.array_equal(scales[ridx].cpu().numpy(), want["scales"])
+    assert np.array_equal(codes[ridx].cpu().numpy(), want["codes"])
+    assert np.array_equal(scores[ridx].cpu().numpy().view(np.uint32), want["scores"].view(np.uint32))
+
+
 def test_quantize_activations_fc2_input():
     x = synth.activations(1024, 11008, 0, 5, kind="silu_gate")
     _run_act_case(x, synth.fisher_per_channel(11008, 0, 6), 0.1, "fc2-X", bf16=True)
