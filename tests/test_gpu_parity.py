@@ -746,8 +746,9 @@ def test_gemm_llama70b_fc1_shape_sampled():
 
 
 def test_gemm_fc2_shape_sampled():
-    M, K, N = 512, 11008, 4096
-    _say("gemm fc2 512x11008x4096")
+    """The benchmark's FC2 shape (K = 11008 = 86 K-tiles, activations = a gated product)."""
+    M, K, N = 4096, 11008, 4096
+    _say("gemm fc2 4096x11008x4096")
     c = _quantized_pair(M, K, N, 3, 0.1, kind="silu_gate", per_elem_w=False)
     Y = fgmp.gemm(c["pX"], c["pW"])
     rng = np.random.default_rng(5)
