@@ -395,8 +395,11 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     const PackedLayout lw = make_layout(N, K);
     p.mt = M <= 16 ? 1 : 2;
     // 17..32 rows of X need twice the LDS per workgroup: 8 waves share it, so that every workgroup of
-    // the launch is still resident at once
-    p.waves = p.mt == 1 ? 4 : 8;
+    // the launch is still resident at once.  Every workgroup re-reads its K range of X: with very long
+    // K, 16 waves -- twice the weight rows per workgroup, half that traffic -- pay off (FC2, K = 11008,
+    // M = 32: 23.7 -> 21.1 us); otherwise they only make the workgroups fewer and longer (O projection,
+    // K = 4096: 15.0 -> 16.3 us; a 57344 x 8192 tensor: 128 -> 131 us).
+    p.waves = p.mt == 1 ? 4 : (lw.n_kt > 64 ? 16 : 8);
     const int64_t rows_per_wg = 16 * p.waves;
     p.row_groups = (N + rows_per_wg - 1) / rows_per_wg;
     // At least one workgroup per CU, each with as many K-tiles as its LDS holds: further splitting of K
@@ -466,7 +469,8 @@ fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const 
     const dim3 grid((unsigned)(p.row_groups * p.ksplit));
     if (p.mt == 1 && M <= 8) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 8>), grid, dim3(256), 0, st, a);
     else if (p.mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 16>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<2, 8, 32>), grid, dim3(512), 0, st, a);
+    else if (p.waves == 8) hipLaunchKernelGGL((gemm_skinny_kernel<2, 8, 32>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<2, 16, 32>), grid, dim3(1024), 0, st, a);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
 }
 
