@@ -1,4 +1,4 @@
-// Decode-shape (M <= 32 tokens) block-mixed-precision GEMM (Sec. 4.1): the
+// Decode-shape (M <= 32 tokens per launch) block-mixed-precision GEMM (Sec. 4.1): the
 // packed weights are streamed from HBM exactly once and decoded in registers
 // straight into MFMA operands; the few activation rows sit in LDS as FP16.
 //
@@ -422,7 +422,46 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     return p;
 }
 
-size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return skinny_plan(M, N, K).total; }
+// More than 32 rows (up to kSkinnyMaxRows) run as chunks of 32 rows, one launch each, on the same
+// stream: the weights of the later chunks come from the Infinity Cache, and up to three such passes
+// are still faster than the 256-row MFMA tiles of the prefill kernel (Llama-2-7B QKV: 62 us for any
+// M from 33 to 256 there).  Workspace: the chunks' partial sums one after the other, then all of
+// their counters, contiguous, so that one clearing pass covers them.
+constexpr int64_t kSkChunkRows = 32;
+static_assert(kSkinnyMaxRows % kSkChunkRows == 0, "whole chunks");
+constexpr int kSkMaxChunks = (int)(kSkinnyMaxRows / kSkChunkRows);
+
+struct SkinnyChunks {
+    int n;
+    SkinnyPlan plan[kSkMaxChunks];
+    int64_t rows[kSkMaxChunks];
+    size_t off_partial[kSkMaxChunks], off_counters[kSkMaxChunks], counters_begin, n_counters, total;
+};
+
+static SkinnyChunks skinny_chunks(int64_t M, int64_t N, int64_t K)
+{
+    SkinnyChunks c;
+    c.n = (int)((M + kSkChunkRows - 1) / kSkChunkRows);
+    size_t off = 0;
+    for (int i = 0; i < c.n; ++i) {
+        c.rows[i] = M - i * kSkChunkRows < kSkChunkRows ? M - i * kSkChunkRows : kSkChunkRows;
+        c.plan[i] = skinny_plan(c.rows[i], N, K);
+        c.off_partial[i] = off;
+        off += c.plan[i].off_counters - c.plan[i].off_partial;   // the chunk's partial sums
+    }
+    c.counters_begin = off;
+    c.n_counters = 0;
+    for (int i = 0; i < c.n; ++i) {
+        c.off_counters[i] = off;
+        const size_t bytes = c.plan[i].total - c.plan[i].off_counters;
+        off += bytes;
+        c.n_counters += bytes / sizeof(uint32_t);
+    }
+    c.total = off;
+    return c;
+}
+
+size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return skinny_chunks(M, N, K).total; }
 
 bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K)
 {
@@ -431,15 +470,18 @@ bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K)
     return M <= kSkinnyMaxRows && make_layout(N, K).total_bytes < kLimit && make_layout(M, K).total_bytes < kLimit;
 }
 
-int64_t gemm_skinny_x16_rows(int64_t M) { return M <= 16 ? 16 : 32; }
+int64_t gemm_skinny_x16_rows(int64_t M)
+{
+    return M <= 16 ? 16 : (M + kSkChunkRows - 1) / kSkChunkRows * kSkChunkRows;
+}
 
-// The arrival counters of a call must be zero when the kernel starts: the caller clears
+// The arrival counters of a call must be zero when the kernels start: the caller clears
 // gemm_skinny_counters(...) words in the kernel that prepares x16 (same stream).
 SkinnyCounters gemm_skinny_counters(int64_t M, int64_t N, int64_t K, void *workspace)
 {
-    const SkinnyPlan p = skinny_plan(M, N, K);
-    return SkinnyCounters{reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + p.off_counters),
-                          p.ksplit > 1 ? p.row_groups * p.waves : 0};
+    const SkinnyChunks c = skinny_chunks(M, N, K);
+    return SkinnyCounters{reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + c.counters_begin),
+                          (int64_t)c.n_counters};
 }
 
 fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const _Float16 *x16, int64_t ld16,
@@ -447,31 +489,38 @@ fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const 
                           int64_t ldy, void *workspace, hipStream_t st)
 {
     if (!gemm_skinny_applies(M, N, K)) return FGMP_ERR_UNSUPPORTED;
-    const SkinnyPlan p = skinny_plan(M, N, K);
+    const SkinnyChunks ch = skinny_chunks(M, N, K);
     char *ws = static_cast<char *>(workspace);
-    const size_t partial_bytes = p.off_counters - p.off_partial;
-    if (p.row_groups * p.ksplit > 0x7FFFFFFF || partial_bytes > 0x7FFFFFFFu)
-        return FGMP_ERR_UNSUPPORTED;
     if (!xh || !x16 || ld16 < lx.n_kt * kTileK || (uintptr_t)x16 % 16 != 0 || (ld16 * 2) % 16 != 0)
         return FGMP_ERR_BAD_SHAPE;
-    SkinnyArgs a;
-    a.w = w; a.xh = xh;
-    a.x16 = x16; a.ld16 = ld16;
-    a.w_rows = lw.rows; a.w_K = lw.K; a.x_rows = lx.rows; a.x_K = lx.K;
-    a.off_L = (uint32_t)lw.off_L; a.off_S = (uint32_t)lw.off_S; a.off_M = (uint32_t)lw.off_M;
-    a.off_T = (uint32_t)lw.off_T; a.off_H = (uint32_t)lw.off_H; a.n_tiles = (uint32_t)lw.n_tiles;
-    a.n_kt = (int)lw.n_kt;
-    a.cols_per_wg = p.cols_per_wg; a.ksplit = p.ksplit;
-    a.partial = reinterpret_cast<float *>(ws + p.off_partial);
-    a.partial_bytes = (uint32_t)partial_bytes;
-    a.counters = reinterpret_cast<uint32_t *>(ws + p.off_counters);
-    a.Y = Y; a.ldy = ldy; a.M = M; a.N = N;
-    const dim3 grid((unsigned)(p.row_groups * p.ksplit));
-    if (p.mt == 1 && M <= 8) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 8>), grid, dim3(256), 0, st, a);
-    else if (p.mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 16>), grid, dim3(256), 0, st, a);
-    else if (p.waves == 8) hipLaunchKernelGGL((gemm_skinny_kernel<2, 8, 32>), grid, dim3(512), 0, st, a);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<2, 16, 32>), grid, dim3(1024), 0, st, a);
-    return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
+    for (int i = 0; i < ch.n; ++i) {
+        const SkinnyPlan &p = ch.plan[i];
+        if (p.row_groups * p.ksplit > 0x7FFFFFFF || p.off_counters - p.off_partial > 0x7FFFFFFFu)
+            return FGMP_ERR_UNSUPPORTED;
+    }
+    for (int i = 0; i < ch.n; ++i) {
+        const SkinnyPlan &p = ch.plan[i];
+        const int64_t rows = ch.rows[i];
+        SkinnyArgs a;
+        a.w = w; a.xh = xh;
+        a.x16 = x16 + i * kSkChunkRows * ld16; a.ld16 = ld16;
+        a.w_rows = lw.rows; a.w_K = lw.K; a.x_rows = lx.rows; a.x_K = lx.K;
+        a.off_L = (uint32_t)lw.off_L; a.off_S = (uint32_t)lw.off_S; a.off_M = (uint32_t)lw.off_M;
+        a.off_T = (uint32_t)lw.off_T; a.off_H = (uint32_t)lw.off_H; a.n_tiles = (uint32_t)lw.n_tiles;
+        a.n_kt = (int)lw.n_kt;
+        a.cols_per_wg = p.cols_per_wg; a.ksplit = p.ksplit;
+        a.partial = reinterpret_cast<float *>(ws + ch.off_partial[i]);
+        a.partial_bytes = (uint32_t)(p.off_counters - p.off_partial);
+        a.counters = reinterpret_cast<uint32_t *>(ws + ch.off_counters[i]);
+        a.Y = Y + i * kSkChunkRows * ldy; a.ldy = ldy; a.M = rows; a.N = N;
+        const dim3 grid((unsigned)(p.row_groups * p.ksplit));
+        if (p.mt == 1 && rows <= 8) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 8>), grid, dim3(256), 0, st, a);
+        else if (p.mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<1, 4, 16>), grid, dim3(256), 0, st, a);
+        else if (p.waves == 8) hipLaunchKernelGGL((gemm_skinny_kernel<2, 8, 32>), grid, dim3(512), 0, st, a);
+        else hipLaunchKernelGGL((gemm_skinny_kernel<2, 16, 32>), grid, dim3(1024), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return FGMP_ERR_HIP;
+    }
+    return FGMP_OK;
 }
 
 }  // namespace fgmp

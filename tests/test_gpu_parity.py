@@ -760,11 +760,12 @@ def test_gemm_fc2_shape_sampled():
 @pytest.mark.parametrize("M,K,N,p", [(1, 4096, 4096, 0.1), (8, 4096, 4096, 0.1), (32, 4096, 4096, 0.1),
                                      (17, 11008, 4096, 0.1), (5, 304, 100, 0.3), (32, 1024, 72, 1.0),
                                      (16, 2048, 264, 0.5), (3, 4096, 12288, 0.0), (5, 4096, 14000, 0.1),
-                                     (9, 11008, 8200, 0.2)])
+                                     (9, 11008, 8200, 0.2), (33, 1024, 520, 0.1), (64, 4096, 4096, 0.1),
+                                     (96, 2048, 264, 0.3), (70, 11008, 4096, 0.1), (41, 304, 100, 1.0)])
 def test_gemm_decode_shapes(M, K, N, p):
-    """Weight-streaming path (M <= 32): K ranges combined in K order, ragged N and
-    K, FP8 fractions beyond the speculative plane-H window, and weight tensors with
-    so many rows that workgroups take 128 instead of 64 of them."""
+    """Weight-streaming path (M <= 96, in chunks of 32 rows): K ranges combined in K order, ragged N
+    and K, FP8 fractions beyond the speculative plane-H window, weight tensors with so many rows that
+    workgroups take 128 instead of 64 of them, last chunks of 1, 9, 6 and 32 rows."""
     _say(f"gemm decode M={M} K={K} N={N} p={p}")
     c = _quantized_pair(M, K, N, 11, p, per_elem_w=False)
     Y = fgmp.gemm(c["pX"], c["pW"])
@@ -852,12 +853,12 @@ def test_gemm_kernel_timing_hook():
     assert ea.elapsed_time(eb) == ms
 
 
-@pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (300, 512, 520)])
+@pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (300, 512, 520), (70, 1024, 512)])
 def test_fused_call_replays_in_a_hip_graph(M, K, N):
     """The hot-path calls only enqueue kernels on the caller's stream (no allocation, no synchronization,
     no memset nodes: arrival counters are cleared by the kernel that prepares the activations), so a
-    captured step can be replayed: a decode shape (split-K counters) and a prefill shape whose tiles are
-    computed in two parts.  Every replay, with eager work and synchronizations in between, must
+    captured step can be replayed: a decode shape (split-K counters), a prefill shape whose tiles are
+    computed in two parts, and a decode shape of three row chunks.  Every replay, with eager work and synchronizations in between, must
     reproduce the eager result bit for bit."""
     c = _quantized_pair(M, K, N, 43, 0.1, per_elem_w=False)
     ws = torch.empty(fgmp.workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
