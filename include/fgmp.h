@@ -175,8 +175,8 @@ fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M
  * columns (= 16 consecutive input channels of the next layer) is scored (Eq. 6) with `fisher_n`,
  * compared with `threshold_y` and stored as FP8 or NVFP4 in `packed_Y`, a packed M x N activation
  * tensor (tensor scale `scale_y`) that the next layer's fgmp_gemm consumes.  The values that are
- * quantized are exactly the FP32 numbers fgmp_quant_gemm_fused would have written.  For M > 96 this
- * happens in the GEMM kernel's epilogue; smaller M stage the FP32 results in the workspace.
+ * quantized are exactly the FP32 numbers fgmp_quant_gemm_fused would have written.  For shapes that
+ * run on the prefill kernel this happens in its epilogue; small M stage the FP32 results in the workspace.
  *   fisher_n   N FP32 sensitivities; N % 16 == 0
  *   packed_Y   out, packed_Y_bytes >= fgmp_packed_bytes(M, N); scores_y nullable, M*N/16 FP32
  *   workspace  >= fgmp_workspace_bytes_packed_out(M, N, K)

@@ -422,11 +422,13 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
     return p;
 }
 
-// More than 32 rows (up to kSkinnyMaxRows) run as chunks of 32 rows, one launch each, on the same
-// stream: the weights of the later chunks come from the Infinity Cache, and up to three such passes
-// are still faster than the 256-row MFMA tiles of the prefill kernel (Llama-2-7B QKV: 62 us for any
-// M from 33 to 256 there).  Workspace: the chunks' partial sums one after the other, then all of
-// their counters, contiguous, so that one clearing pass covers them.
+// More than 32 rows (up to kSkinnyMaxRows) may run as chunks of 32 rows, one launch each, on the same
+// stream: the weights of the later chunks come from the Infinity Cache, and a few such passes are
+// faster than the 256-row MFMA tiles of the prefill kernel, whose time hardly depends on M below 256
+// (Llama-2-7B, microseconds per fused step at M = 33 / 64 / 96 in chunks against the prefill kernel:
+// QKV 31 / 35 / 49 against 62, O 22 / 24 / 34 against 59, FC2 35 / 39 / 55 against 137, FC1 47 / 55 /
+// 78 against 64).  Workspace: the chunks' partial sums one after the other, then all of their
+// counters, contiguous, so that one clearing pass covers them.
 constexpr int64_t kSkChunkRows = 32;
 static_assert(kSkinnyMaxRows % kSkChunkRows == 0, "whole chunks");
 constexpr int kSkMaxChunks = (int)(kSkinnyMaxRows / kSkChunkRows);
@@ -463,11 +465,32 @@ static SkinnyChunks skinny_chunks(int64_t M, int64_t N, int64_t K)
 
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return skinny_chunks(M, N, K).total; }
 
+// Whether n chunks beat the prefill kernel, from a cost model fitted to the measurements above (times in
+// microseconds).  One 32-row pass: a fixed 8 us plus the packed weights at 2.5 TB/s; later passes cost
+// 0.65 of that while the weights fit the Infinity Cache.  Prefill kernel below 257 rows: one tile per
+// 256 weight rows, two workgroups per tile when that fills at most half the chip (the longer one takes
+// 9/16 of the K-steps), 1.45 us per K-step of 64, rounds of 256 workgroups.
+static bool chunks_beat_prefill_kernel(int64_t n_chunks, int64_t N, int64_t K)
+{
+    const double w_bytes = 0.62 * (double)N * (double)K;
+    const double pass = 8.0 + w_bytes / 2.5e6;
+    const double t_chunks = 5.0 + pass * (1.0 + (w_bytes < 200e6 ? 0.65 : 1.0) * (double)(n_chunks - 1));
+    const int64_t tiles = (N + 255) / 256, nk = (K + 127) / 128 * 2;
+    const bool split = tiles % 256 <= 128 && nk >= 4;
+    const int64_t units = split ? 2 * tiles : tiles;
+    const double steps = split ? (double)nk * 9.0 / 16.0 : (double)nk;
+    const double t_prefill = 10.0 + (double)((units + 255) / 256) * steps * 1.45;
+    return t_chunks < t_prefill;
+}
+
 bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K)
 {
     // buffer loads address the packed tensors with 32-bit offsets
     constexpr uint64_t kLimit = 0xFFFFFF00ull;
-    return M <= kSkinnyMaxRows && make_layout(N, K).total_bytes < kLimit && make_layout(M, K).total_bytes < kLimit;
+    if (M > kSkinnyMaxRows || make_layout(N, K).total_bytes >= kLimit || make_layout(M, K).total_bytes >= kLimit)
+        return false;
+    const int64_t n_chunks = (M + kSkChunkRows - 1) / kSkChunkRows;
+    return n_chunks == 1 || chunks_beat_prefill_kernel(n_chunks, N, K);
 }
 
 int64_t gemm_skinny_x16_rows(int64_t M)

@@ -44,7 +44,7 @@ fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, i
 // Decode shapes (few rows of X): weight-streaming kernel.  X is given as FP16 values (`x16`,
 // gemm_skinny_x16_rows(M) rows of ld16 halves; rows from M rounded up to 8 on are never used for a
 // stored output) plus the header of its packed form.
-constexpr int64_t kSkinnyMaxRows = 96;   // in chunks of 32 rows, one launch each
+constexpr int64_t kSkinnyMaxRows = 256;   // in chunks of 32 rows, one launch each, while that beats the prefill kernel
 bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K);
 int64_t gemm_skinny_x16_rows(int64_t M);
 size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K);

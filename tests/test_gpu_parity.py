@@ -415,7 +415,7 @@ def _exact_product_case(M, K, N, seed):
 @pytest.mark.parametrize("M,K,N", [(136, 128, 272), (300, 64, 512), (257, 128, 48), (24, 128, 160)])
 def test_fused_packed_output_matches_oracle(M, K, N):
     """GEMM whose results are scored, quantized and packed before they reach memory: codes, block
-    scales, decisions and scores equal the oracle's quantization of the oracle's product (M > 96: in
+    scales, decisions and scores equal the oracle's quantization of the oracle's product (larger M: in
     the GEMM epilogue; M = 24: staged through FP32)."""
     _say(f"packed output M={M} K={K} N={N}")
     x, w, ones, y32 = _exact_product_case(M, K, N, 31)
@@ -470,7 +470,7 @@ def test_packed_output_on_random_inputs_is_consistent(M, K, N):
 def test_fused_gated_packed_output_matches_oracle(M, K, N):
     """The same with the gated activation in front of the quantizer: what is scored, quantized and packed
     is SiLU(gate) * up of the 32 + 32 row groups of W, as the oracle computes it from its own product
-    (M > 96: in the GEMM epilogue; M = 24: staged through FP32)."""
+    (larger M: in the GEMM epilogue; M = 24: staged through FP32)."""
     _say(f"gated packed output M={M} K={K} N={N}")
     x, w, ones, y32 = _exact_product_case(M, K, N, 37)
     h32 = orc.gate_columns(y32)
@@ -763,7 +763,7 @@ def test_gemm_fc2_shape_sampled():
                                      (9, 11008, 8200, 0.2), (33, 1024, 520, 0.1), (64, 4096, 4096, 0.1),
                                      (96, 2048, 264, 0.3), (70, 11008, 4096, 0.1), (41, 304, 100, 1.0)])
 def test_gemm_decode_shapes(M, K, N, p):
-    """Weight-streaming path (M <= 96, in chunks of 32 rows): K ranges combined in K order, ragged N
+    """Weight-streaming path (M <= 32 per launch; more rows in chunks of 32 where that is the faster path): K ranges combined in K order, ragged N
     and K, FP8 fractions beyond the speculative plane-H window, weight tensors with so many rows that
     workgroups take 128 instead of 64 of them, last chunks of 1, 9, 6 and 32 rows."""
     _say(f"gemm decode M={M} K={K} N={N} p={p}")
