@@ -294,7 +294,7 @@ fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W,
         if (tiles_m * tiles_n > 0x7FFFFFFF) return FGMP_ERR_UNSUPPORTED;
         const DecodeJob jx = make_decode_job(A, la, x16, w.ld, w.Mp / kTileRows);
         const SplitTail sp = plan_split_tail(tiles_m * tiles_n, (int)(w.ld / kBK), static_cast<char *>(workspace) + w.off_split);
-        const fgmp_status_t rcx = launch_decode_f16(jx, nullptr, sp.counters, (int64_t)sp.n_split, st);
+        const fgmp_status_t rcx = launch_decode_f16(jx, nullptr, sp.counters, (int64_t)sp.n_counters, st);
         if (rcx != FGMP_OK) return rcx;
         launch_gemm_mixed(x16, w.ld, B, lb, Y, ldy, M, N, tiles_m, tiles_n, A.hdr, st, sp);
         return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;
@@ -354,7 +354,7 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
         const SplitTail sp = plan_split_tail(tiles_m * tiles_n, (int)(w.ld / kBK), split_region);
         const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws,
                                                  sizeof(PackedHeader), nullptr, false, st, x16, w.ld, sp.counters,
-                                                 (int64_t)sp.n_split, score_mode);
+                                                 (int64_t)sp.n_counters, score_mode);
         if (rc != FGMP_OK) return rc;
         const PackedLayout lb = make_layout(N, K);
         const PackedView B = make_view(const_cast<void *>(packed_W), lb);

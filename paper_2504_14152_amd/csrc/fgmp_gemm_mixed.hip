@@ -110,15 +110,15 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / kWN, wn = wave % kWN;
     // Workgroups [0, n_whole) compute one tile each over all of K.  The tiles beyond -- a last, partly
-    // filled round of the chip -- are split in two along K: workgroup n_whole + u takes tile
-    // n_whole + u % n_split, K-steps [0, kt_split) if u < n_split and [kt_split, nk_total) otherwise.
+    // filled round of the chip -- are split in n_parts along K: workgroup n_whole + u takes tile
+    // n_whole + u % n_split and part u / n_split of its K-steps.
     int64_t tm, tn;
     const int unit = (int)blockIdx.x - sp.n_whole;
     const bool split = unit >= 0;
-    const int split_tile = split ? unit % sp.n_split : 0, upper = split && unit >= sp.n_split;
+    const int split_tile = split ? unit % sp.n_split : 0, part = split ? unit / sp.n_split : 0;
     tile_coords(split ? sp.n_whole + split_tile : (int64_t)blockIdx.x, n_tm, n_tn, tm, tn);
-    const int kt0 = upper ? sp.kt_split : 0;                                    // first K-step of this workgroup
-    const int nk = split ? (upper ? nk_total - sp.kt_split : sp.kt_split) : nk_total;   // and how many
+    const int kt0 = split ? sp.kt_bound[part] : 0;                          // first K-step of this workgroup
+    const int nk = split ? sp.kt_bound[part + 1] - kt0 : nk_total;          // and how many
 
     // ---- A: direct global -> LDS, chunk swizzle applied on the global side.  The address is a uniform
     // base (tile row, K-step) plus a per-lane 32-bit offset that never changes, so the loop spends no
@@ -345,50 +345,61 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
     const bool w_ok = W.hdr->magic == kMagic && W.hdr->rows == lw.rows && W.hdr->K == lw.K;
     const float ss = w_ok ? ha->tensor_scale * W.hdr->tensor_scale : 0.0f;
     if (split) {
-        // The two parts of a tile meet here.  A workgroup that finds the tile's counter at 1 knows the
-        // other part's accumulators are in memory, complete: it adds them to its own and goes on to the
-        // epilogue.  Otherwise every wave stores its accumulators (layout [tile][part][wave][register
-        // quad][lane], 16 bytes per lane and store); when all of the workgroup's stores are complete, one
-        // thread bumps the counter; if the other part arrived meanwhile (both stored), the workgroup that
-        // bumped second finishes the tile, the other one is done.  a + b = b + a exactly, so the result does
-        // not depend on the order of arrival.  The first part is the shorter one and is launched first, so
-        // it normally is in memory when the second needs it, off the critical path.  Partials and counter
-        // cross XCDs: system-coherent accesses that bypass the per-XCD L2.
+        // Two workgroups that hold partial sums of the same tile meet (`meet` below).  One that finds the
+        // meeting's counter at 1 knows the other's accumulators are in memory, complete: it adds them to
+        // its own and goes on.  Otherwise every wave stores its accumulators (16 bytes per lane and
+        // store, [slot][wave][register quad][lane]); when all of the workgroup's stores are complete, one
+        // thread bumps the counter; if the other arrived meanwhile (both stored), the workgroup that
+        // bumped second goes on with the sum, the other one is done.  a + b = b + a exactly, so the result
+        // does not depend on the order of arrival.  With two parts the first is the shorter one and is
+        // launched first, so it normally is in memory when the second needs it, off the critical path.
+        // With four parts, parts 0, 1 and 2, 3 meet first, then the two pair sums: (p0 + p1) + (p2 + p3)
+        // whatever the order.  Partials and counters cross XCDs: system-coherent accesses that bypass the
+        // per-XCD L2.
         constexpr uint32_t kWaveBytes = TM * TN * 4 * 1024;
         const __amdgpu_buffer_rsrc_t pbuf =
             __builtin_amdgcn_make_buffer_rsrc(sp.partial, 0, (int)sp.partial_bytes, 0x00020000);
-        const uint32_t mine = (uint32_t)((split_tile * 2 + upper) * kWaves + wave) * kWaveBytes + lane * 16u;
-        const uint32_t other = (uint32_t)((split_tile * 2 + (upper ^ 1)) * kWaves + wave) * kWaveBytes + lane * 16u;
         uint32_t *arrived = reinterpret_cast<uint32_t *>(&lds[0][0][0]);   // the operand stages are free now
-        __syncthreads();
-        if (tid == 0) *arrived = __hip_atomic_load(&sp.counters[split_tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (*arrived == 0u) {
+        auto meet = [&](int counter, int my_slot, int other_slot) {
+            const uint32_t mine = (uint32_t)(my_slot * kWaves + wave) * kWaveBytes + lane * 16u;
+            const uint32_t other = (uint32_t)(other_slot * kWaves + wave) * kWaveBytes + lane * 16u;
+            __syncthreads();
+            if (tid == 0) *arrived = __hip_atomic_load(&sp.counters[counter], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (*arrived == 0u) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            store_coherent16(pbuf, mine + ((i * TN + j) * 4 + q) * 1024u,
+                                             float4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]});
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();   // all stores of the workgroup are complete (and everyone has read *arrived)
+                if (tid == 0)
+                    *arrived = __hip_atomic_fetch_add(&sp.counters[counter], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                if (*arrived == 0u) return false;
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        store_coherent16(pbuf, mine + ((i * TN + j) * 4 + q) * 1024u,
-                                         float4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]});
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();   // all stores of the workgroup are complete (and everyone has read *arrived)
-            if (tid == 0)
-                *arrived = __hip_atomic_fetch_add(&sp.counters[split_tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            if (*arrived == 0u) return;
-        }
+                    for (int q = 0; q < 4; ++q) {
+                        const float4_t o = load_coherent16(pbuf, other + ((i * TN + j) * 4 + q) * 1024u);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4_t o = load_coherent16(pbuf, other + ((i * TN + j) * 4 + q) * 1024u);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
-                }
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
+                    }
+            return true;
+        };
+        const bool four = sp.n_parts == 4;
+        const int slots = four ? 6 : 2, counters = four ? 3 : 1;   // per tile
+        if (!meet(split_tile * counters + (part >> 1), split_tile * slots + part, split_tile * slots + (part ^ 1))) return;
+        if (four && !meet(split_tile * counters + 2, split_tile * slots + 4 + (part >> 1),
+                          split_tile * slots + 4 + ((part >> 1) ^ 1)))
+            return;
     }
     if constexpr (!kPackOut) {
 #pragma unroll
@@ -492,11 +503,12 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
 }
 
 // A tile keeps a compute unit busy for one "round"; the chip runs kNumCu tiles per round.  When the
-// last round is at most half full, its tiles are split in two along K: two half-length workgroups per
-// tile still fit one round, which then takes half the time (4096 x 22016: 1376 tiles = 5 rounds + 96
-// tiles; 6 rounds become 5.5).  Fuller last rounds, and K ranges too short to halve, are left alone.
+// last round is at most half full, its tiles are split along K: two shorter workgroups per tile still
+// fit one round, which then takes about half the time (4096 x 22016: 1376 tiles = 5 rounds + 96 tiles;
+// 6 rounds become 5.5) -- four when the round is at most a quarter full (small M: a QKV product of
+// 256 rows has 48 tiles).  Fuller last rounds, and K ranges too short to divide, are left alone.
 constexpr int64_t kNumCu = 256;
-constexpr size_t kSplitTileBytes = 2 * (size_t)kBM * kBN * 4;          // both halves' accumulators of one tile
+constexpr size_t kSplitSlotBytes = (size_t)kBM * kBN * 4;   // the accumulators of one workgroup
 
 static int64_t split_tiles(int64_t n_tiles)
 {
@@ -507,7 +519,9 @@ static int64_t split_tiles(int64_t n_tiles)
 size_t gemm_mixed_split_bytes(int64_t n_tiles)
 {
     const int64_t n = split_tiles(n_tiles);
-    return n == 0 ? 0 : (size_t)n * kSplitTileBytes + (size_t)align_up((uint64_t)n * 4, 256);
+    if (n == 0) return 0;
+    const bool four = n <= kNumCu / 4;   // (sized for four parts even when K turns out too short for them)
+    return (size_t)n * (four ? 6 : 2) * kSplitSlotBytes + (size_t)align_up((uint64_t)n * (four ? 3 : 1) * 4, 256);
 }
 
 SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region)
@@ -520,10 +534,20 @@ SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region)
     }
     sp.n_whole = (int)(n_tiles - n);
     sp.n_split = (int)n;
-    // even (a K-step pair is one 128-element tile of the packed layout), and somewhat less than half: the
-    // first part is done, and in memory, before the second one asks for it
-    sp.kt_split = ((nk * 7 / 16) & ~1) >= 2 ? (nk * 7 / 16) & ~1 : 2;
-    sp.partial_bytes = (uint32_t)((size_t)n * kSplitTileBytes);
+    // K-step pairs are 128-element tiles of the packed layout: every boundary is even
+    if (n <= kNumCu / 4 && nk >= 8) {
+        sp.n_parts = 4;
+        for (int p = 0; p <= 4; ++p) sp.kt_bound[p] = p == 4 ? nk : (nk * p / 4) & ~1;
+    } else {
+        // somewhat less than half: the first part is done, and in memory, before the second one asks for it
+        sp.n_parts = 2;
+        sp.kt_bound[0] = 0;
+        sp.kt_bound[1] = ((nk * 7 / 16) & ~1) >= 2 ? (nk * 7 / 16) & ~1 : 2;
+        sp.kt_bound[2] = nk;
+    }
+    const bool four = sp.n_parts == 4;
+    sp.n_counters = (int)n * (four ? 3 : 1);
+    sp.partial_bytes = (uint32_t)((size_t)n * (four ? 6 : 2) * kSplitSlotBytes);
     sp.partial = static_cast<float *>(region);
     sp.counters = reinterpret_cast<uint32_t *>(static_cast<char *>(region) + sp.partial_bytes);
     return sp;
@@ -541,7 +565,7 @@ void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, con
                        hipStream_t st, const SplitTail &sp, const PackOut *pack_out)
 {
     if (g_ev_start) (void)hipEventRecord(g_ev_start, st);
-    const unsigned grid = (unsigned)(sp.n_whole + 2 * sp.n_split);
+    const unsigned grid = (unsigned)(sp.n_whole + sp.n_parts * sp.n_split);
 #ifndef FGMP_MIXED_WM
 #define FGMP_MIXED_WM 2
 #define FGMP_MIXED_WN 4

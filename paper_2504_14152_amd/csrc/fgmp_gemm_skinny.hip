@@ -469,17 +469,19 @@ size_t gemm_skinny_workspace_bytes(int64_t M, int64_t N, int64_t K) { return ski
 // microseconds).  One 32-row pass: a fixed 8 us plus the packed weights at 2.5 TB/s; later passes cost
 // 0.65 of that while the weights fit the Infinity Cache.  Prefill kernel below 257 rows: one tile per
 // 256 weight rows, two workgroups per tile when that fills at most half the chip (the longer one takes
-// 9/16 of the K-steps), 1.45 us per K-step of 64, rounds of 256 workgroups.
+// 9/16 of the K-steps), four when at most a quarter (and a second meeting), 1.45 us per K-step of 64,
+// rounds of 256 workgroups.
 static bool chunks_beat_prefill_kernel(int64_t n_chunks, int64_t N, int64_t K)
 {
     const double w_bytes = 0.62 * (double)N * (double)K;
     const double pass = 8.0 + w_bytes / 2.5e6;
     const double t_chunks = 5.0 + pass * (1.0 + (w_bytes < 200e6 ? 0.65 : 1.0) * (double)(n_chunks - 1));
     const int64_t tiles = (N + 255) / 256, nk = (K + 127) / 128 * 2;
-    const bool split = tiles % 256 <= 128 && nk >= 4;
-    const int64_t units = split ? 2 * tiles : tiles;
-    const double steps = split ? (double)nk * 9.0 / 16.0 : (double)nk;
-    const double t_prefill = 10.0 + (double)((units + 255) / 256) * steps * 1.45;
+    const int64_t tail = tiles % 256;
+    const int parts = tail <= 64 && nk >= 8 ? 4 : (tail <= 128 && nk >= 4 ? 2 : 1);
+    const int64_t units = parts * tiles;
+    const double steps = parts == 4 ? (double)nk / 4.0 : (parts == 2 ? (double)nk * 9.0 / 16.0 : (double)nk);
+    const double t_prefill = (parts == 4 ? 16.0 : 10.0) + (double)((units + 255) / 256) * steps * 1.45;
     return t_chunks < t_prefill;
 }
 

@@ -77,20 +77,22 @@ struct PackOut {
     float *scores;         // nullable, M * N / 16
     int gate;              // nonzero: quantize SiLU(gate) * up of the 32 + 32 row groups of W; `out` is M x N / 2
 };
-// The last, partly filled round of tiles of the prefill kernel, split in two along K (n_split 0: no split).
+// The last, partly filled round of tiles of the prefill kernel, split along K (n_split 0: no split).
 struct SplitTail {
     int n_whole;              // workgroups [0, n_whole) compute whole tiles
-    int n_split;              // tiles n_whole .. n_whole + n_split - 1 are computed by two workgroups each
-    int kt_split;             // the first covers K-steps [0, kt_split), the second the rest (kt_split even)
-    uint32_t partial_bytes;   // n_split * 2 * 256 KB
-    float *partial;           // accumulators of the halves, 16-byte aligned
-    uint32_t *counters;       // n_split arrival counters, zero at launch
+    int n_split;              // tiles n_whole .. n_whole + n_split - 1 are computed by n_parts workgroups each
+    int n_parts;              // 2, or 4 when that still fits one round of the chip
+    int kt_bound[5];          // part p covers K-steps [kt_bound[p], kt_bound[p + 1]) (all even)
+    int n_counters;           // n_split, or 3 n_split with four parts (two pairs, then the pair sums)
+    uint32_t partial_bytes;   // n_split * 256 KB * (2, or 6 with four parts: 4 parts + 2 pair sums)
+    float *partial;           // accumulators of the parts, 16-byte aligned
+    uint32_t *counters;       // arrival counters, zero at launch
 };
 // Workspace bytes the split of `n_tiles` output tiles needs (0: no split), and the split itself with its
 // buffers at `region` (that many bytes, 256-byte aligned); `nk` K-steps of 64.
 size_t gemm_mixed_split_bytes(int64_t n_tiles);
 SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region);
-// `sp.counters` (sp.n_split words) must be zero when the kernel starts
+// `sp.counters` (sp.n_counters words) must be zero when the kernel starts
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
                        hipStream_t st, const SplitTail &sp, const PackOut *pack_out = nullptr);
