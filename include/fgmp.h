@@ -131,9 +131,9 @@ fgmp_status_t fgmp_quantize_activations(const void *X, fgmp_dtype_t dt, int64_t 
  *   Y          out, M x N FP32, leading dimension ldy >= N
  *   workspace  >= fgmp_workspace_bytes(M, N, K) bytes of scratch (the decoded
  *              FP16 operands live here during the call, and the partial sums and
- *              arrival counters of output tiles that two workgroups compute
- *              together: calls that may overlap in time need workspaces of
- *              their own)
+ *              arrival counters of output tiles that several workgroups
+ *              compute together: calls that may overlap in time need
+ *              workspaces of their own)
  * Operands whose headers do not match (M, K) / (N, K) are treated as zeros
  * (the planes of fixed extent -- all but the FP8 upper halves -- are still read
  * at the offsets (M, K) / (N, K) imply, so each buffer must hold a packed tensor

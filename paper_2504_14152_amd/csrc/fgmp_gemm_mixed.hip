@@ -27,8 +27,9 @@
 //
 // One workgroup computes one 256 x 256 output tile over all of K -- except the
 // tiles of a last round that fills at most half of the chip: those are
-// computed by two workgroups each, over complementary K ranges, which meet
-// through the workspace after their loops (see SplitTail).
+// computed by two (at most a quarter: four) workgroups each, over
+// complementary K ranges, which meet pairwise through the workspace after
+// their loops (see SplitTail).
 #include <type_traits>
 
 #include "fgmp_elementwise.hpp"
