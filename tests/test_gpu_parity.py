@@ -664,11 +664,12 @@ def test_fused_prefill_saturating_tensor_scale(dtype):
     assert torch.equal(Y, Yf)
 
 
-def test_gemm_split_last_round_sampled():
-    """272 output tiles: 256 computed whole, the 16 of the partly filled last round in two parts along K
-    (2 + 6 K-steps) that meet through the workspace.  Rows and columns are drawn from every tile."""
-    M, K, N = 4352, 512, 4096
-    _say("gemm 4352x512x4096: whole tiles and split tiles in one launch")
+@pytest.mark.parametrize("M,K,N", [(4352, 512, 4096), (2304, 256, 2304), (2304, 128, 2304)])
+def test_gemm_split_last_round_sampled(M, K, N):
+    """Tiles of a partly filled last round are computed in parts along K that meet through the workspace:
+    272 tiles = 256 whole + 16 in four parts of two K-steps; 81 tiles, all in two parts; and a K too short to
+    divide (whole tiles only).  Rows and columns are drawn from every tile."""
+    _say(f"gemm {M}x{K}x{N}: whole tiles and split tiles")
     c = _quantized_pair(M, K, N, 11, 0.2, per_elem_w=False)
     Y = fgmp.gemm(c["pX"], c["pW"])
     rng = np.random.default_rng(77)
@@ -678,7 +679,7 @@ def test_gemm_split_last_round_sampled():
     assert torch.isfinite(Y).all()
     Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
     assert torch.equal(Y, Yf)
-    # the parts of a tile may arrive in either order: a + b = b + a, so repeated calls agree bit for bit
+    # the parts of a tile may arrive in any order: every meeting adds two numbers, so repeated calls agree bit for bit
     for _ in range(3):
         assert torch.equal(Yf, fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"]))
 
