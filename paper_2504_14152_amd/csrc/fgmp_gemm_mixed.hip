@@ -361,6 +361,8 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         const __amdgpu_buffer_rsrc_t pbuf =
             __builtin_amdgcn_make_buffer_rsrc(sp.partial, 0, (int)sp.partial_bytes, 0x00020000);
         uint32_t *arrived = reinterpret_cast<uint32_t *>(&lds[0][0][0]);   // the operand stages are free now
+        // (32-row bands of the tile beyond the tensor's last row are not exchanged: nothing of them is stored)
+        auto band_has_rows = [&](int i) { return tm * kBM + wm * (TM * 32) + i * 32 < M; };
         auto meet = [&](int counter, int my_slot, int other_slot) {
             const uint32_t mine = (uint32_t)(my_slot * kWaves + wave) * kWaveBytes + lane * 16u;
             const uint32_t other = (uint32_t)(other_slot * kWaves + wave) * kWaveBytes + lane * 16u;
@@ -370,12 +372,14 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
             if (*arrived == 0u) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
+                    if (band_has_rows(i)) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
+                        for (int j = 0; j < TN; ++j)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            store_coherent16(pbuf, mine + ((i * TN + j) * 4 + q) * 1024u,
-                                             float4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]});
+                            for (int q = 0; q < 4; ++q)
+                                store_coherent16(pbuf, mine + ((i * TN + j) * 4 + q) * 1024u,
+                                                 float4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]});
+                    }
                 __builtin_amdgcn_s_waitcnt(0);
                 __syncthreads();   // all stores of the workgroup are complete (and everyone has read *arrived)
                 if (tid == 0)
@@ -385,14 +389,16 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
+                if (band_has_rows(i)) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                    for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4_t o = load_coherent16(pbuf, other + ((i * TN + j) * 4 + q) * 1024u);
+                        for (int q = 0; q < 4; ++q) {
+                            const float4_t o = load_coherent16(pbuf, other + ((i * TN + j) * 4 + q) * 1024u);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
-                    }
+                            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
+                        }
+                }
             return true;
         };
         const bool four = sp.n_parts == 4;
