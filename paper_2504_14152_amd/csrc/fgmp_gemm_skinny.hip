@@ -425,9 +425,9 @@ static SkinnyPlan skinny_plan(int64_t M, int64_t N, int64_t K)
 // More than 32 rows (up to kSkinnyMaxRows) may run as chunks of 32 rows, one launch each, on the same
 // stream: the weights of the later chunks come from the Infinity Cache, and a few such passes are
 // faster than the 256-row MFMA tiles of the prefill kernel, whose time hardly depends on M below 256
-// (Llama-2-7B, microseconds per fused step at M = 33 / 64 / 96 in chunks against the prefill kernel:
-// QKV 31 / 35 / 49 against 62, O 22 / 24 / 34 against 59, FC2 35 / 39 / 55 against 137, FC1 47 / 55 /
-// 78 against 64).  Workspace: the chunks' partial sums one after the other, then all of their
+// (Llama-2-7B, microseconds per fused step at M = 33 / 64 / 96 in chunks against the prefill kernel at
+// M = 96 .. 256: QKV 31 / 35 / 49 against 44 .. 56, O 22 / 24 / 34 against 43 .. 49, FC2 35 / 39 / 55
+// against 82 .. 85, FC1 47 / 55 / 78 against 64).  Workspace: the chunks' partial sums one after the other, then all of their
 // counters, contiguous, so that one clearing pass covers them.
 constexpr int64_t kSkChunkRows = 32;
 static_assert(kSkinnyMaxRows % kSkChunkRows == 0, "whole chunks");
