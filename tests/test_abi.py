@@ -77,3 +77,17 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert res.returncode != 0 and "one GPU" in res.stderr
+
+
+def test_workspace_sizes_over_the_row_counts_where_the_paths_change():
+    """Host-side planning only: every M from decode sizes through the first prefill tiles gets a workspace,
+    whichever kernel the planner picks (row chunks through the weight-streaming kernel, tiles split along
+    K, whole tiles), and it never shrinks below what the FP16 copy of X alone needs."""
+    L = fgmp.lib()
+    for (N, K) in [(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008), (264, 2048), (57344, 8192)]:
+        for M in list(range(1, 300)) + [511, 512, 513, 1024, 4096]:
+            ws = int(L.fgmp_workspace_bytes(M, N, K))
+            assert ws >= M * K * 2, (M, N, K, ws)
+            assert ws < (1 << 34), (M, N, K, ws)
+        assert L.fgmp_workspace_bytes(0, N, K) == 0 and L.fgmp_workspace_bytes(8, N, K + 8) == 0
+
