@@ -499,6 +499,25 @@ def main() -> int:
 
     if not args.no_extra:
         extra["gated_mlp_llama2_7b_M4096"] = gated_mlp()
+        # row counts between the decode and the prefill configurations, on the QKV weights (HBM-cold like the
+        # decode steps): 33..256 rows run as 32-row chunks through the weight-streaming kernel or on
+        # 256-row tiles split along K, whichever the library's cost model expects to be faster
+        ncopies = int(600e6 // pW.buf.numel()) + 1
+        pool = [fgmp.Packed(pW.buf.clone(), N, K) for _ in range(ncopies)]
+        small = {}
+        for Ms in (64, 128, 256):
+            xs_ = xd[:Ms].contiguous()
+            Ys = torch.empty((Ms, N), dtype=torch.float32, device=dev)
+            wss = torch.empty(fgmp.workspace_bytes(Ms, N, K), dtype=torch.uint8, device=dev)
+            it = [0]
+
+            def call_small():
+                fgmp.quant_gemm_fused(xs_, fxd, Tx, sx, pool[it[0] % ncopies], out=Ys, workspace=wss)
+                it[0] += 1
+            ms_s = timed(call_small, 40, 5)
+            small[f"M{Ms}"] = {"us_per_step": round(ms_s * 1e3, 1), "TFLOPs": round(2.0 * Ms * N * K / (ms_s * 1e-3) / 1e12, 1)}
+        del pool
+        extra["qkv_between_decode_and_prefill_hbm_cold"] = small
 
     if args.sweep:
         sw_res = {}
