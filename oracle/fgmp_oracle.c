@@ -455,6 +455,29 @@ void fgmp_oracle_silu_mul(const float *g, const float *u, int64_t n, float *h)
     }
 }
 
+/* The same two functions written a second, structurally different way, as
+ * a cross-check of the sequence above (used by the pins only, never by a
+ * parity test): no range reduction, no polynomial -- the C library's fp64
+ * exponential and ONE rounding to fp32 at the very end.  E_ref(x) is the
+ * correctly rounded fp32 value of e^x (x clamped like above); h_ref is the
+ * fp32 nearest to g / (1 + e^-g) * u evaluated in fp64. */
+float fgmp_oracle_exp_rounded_once(float x)
+{
+    double xd = (double)x;
+    if (xd > 88.0) xd = 88.0;
+    if (xd < -87.0) xd = -87.0;
+    return (float)exp(xd);
+}
+
+void fgmp_oracle_silu_mul_rounded_once(const float *g, const float *u, int64_t n, float *h)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const double gd = (double)g[i];
+        h[i] = (float)(gd / (1.0 + exp(-gd)) * (double)u[i]);
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* Threshold for a target fraction of high-precision blocks [Eq. 9]    */
 /* ------------------------------------------------------------------ */

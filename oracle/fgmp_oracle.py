@@ -71,6 +71,10 @@ def _load():
     lib.fgmp_oracle_exp_steps.argtypes = [ctypes.c_float]
     lib.fgmp_oracle_silu_mul.restype = None
     lib.fgmp_oracle_silu_mul.argtypes = [f32p, f32p, i64, f32p]
+    lib.fgmp_oracle_exp_rounded_once.restype = ctypes.c_float
+    lib.fgmp_oracle_exp_rounded_once.argtypes = [ctypes.c_float]
+    lib.fgmp_oracle_silu_mul_rounded_once.restype = None
+    lib.fgmp_oracle_silu_mul_rounded_once.argtypes = [f32p, f32p, i64, f32p]
     lib.fgmp_oracle_threshold.restype = ctypes.c_float
     lib.fgmp_oracle_threshold.argtypes = [f32p, i64, ctypes.c_double]
     lib.fgmp_oracle_storage_bits.restype = i64
@@ -207,6 +211,24 @@ def silu_mul(g: np.ndarray, u: np.ndarray) -> np.ndarray:
         raise ValueError("silu_mul: shapes differ")
     h = np.empty_like(g)
     _load().fgmp_oracle_silu_mul(_ptr(g, ctypes.c_float), _ptr(u, ctypes.c_float), g.size, _ptr(h, ctypes.c_float))
+    return h
+
+
+def exp_rounded_once(x: float) -> float:
+    """e^x (x clamped to [-87, 88]) from the fp64 library exponential, rounded to fp32 once: the
+    cross-check of exp_steps, written without range reduction or polynomial."""
+    return float(_load().fgmp_oracle_exp_rounded_once(float(np.float32(x))))
+
+
+def silu_mul_rounded_once(g: np.ndarray, u: np.ndarray) -> np.ndarray:
+    """The fp32 nearest to g / (1 + e^-g) * u evaluated in fp64: the cross-check of silu_mul."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    if g.shape != u.shape:
+        raise ValueError("silu_mul_rounded_once: shapes differ")
+    h = np.empty_like(g)
+    _load().fgmp_oracle_silu_mul_rounded_once(_ptr(g, ctypes.c_float), _ptr(u, ctypes.c_float), g.size,
+                                              _ptr(h, ctypes.c_float))
     return h
 
 
