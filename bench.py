@@ -35,10 +35,23 @@ PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense FP16/BF16 matrix peak
 PEAK_HBM_GBPS = 8000.0
 P_FP8 = 0.10
 PREHEAT_S = 0.08                # untimed load before the warm-up steps (clock ramp)
-# HBM-side bytes of one gemm_mixed_kernel launch on this workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (KiB per dispatch; FETCH_SIZE reads half of a known-size copy's bytes and is scaled by 2,
-# WRITE_SIZE reads it exactly): see profiles/gemm_mixed_kernel_qkv_prefill_traffic.txt
-GEMM_KERNEL_HBM_BYTES = int((2 * 1.603e5 + 1.966e5) * 1024)
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_mixed_kernel_qkv_prefill_traffic.txt")
+
+
+def traffic_from_profile() -> int:
+    """HBM-side bytes of one gemm_mixed_kernel launch on this workload, read from the committed rocprofv3
+    summary (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
+    copy of known size) -- the line "roofline.traffic: ..." of that file.  Fails loudly when the summary or
+    the line is missing, so the benchmark line cannot drift away from the evidence it cites."""
+    import re
+    with open(TRAFFIC_PROFILE) as fh:
+        text = fh.read()
+    m = re.search(r"^roofline\.traffic:\s*kernel=gemm_mixed_kernel\s+FETCH_SIZE_KiB=([0-9.eE+]+)\s+fetch_scale=([0-9.]+)"
+                  r"\s+WRITE_SIZE_KiB=([0-9.eE+]+)\s+write_scale=([0-9.]+)", text, flags=re.M)
+    if m is None:
+        raise RuntimeError(f"{TRAFFIC_PROFILE} has no 'roofline.traffic:' line")
+    fetch, fs, write, ws_ = (float(g) for g in m.groups())
+    return int((fetch * fs + write * ws_) * 1024)
 
 
 def bytes_per_block(p: float) -> float:
@@ -53,8 +66,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also run the FP8-fraction sweep at the Llama-2-70B FC1 shape (configs[4]; a few GB, ~1 min)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the FP8-fraction sweep at the Llama-2-70B FC1 shape (configs[4]; a few GB, ~1 min)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -63,13 +76,14 @@ def main() -> int:
         return 2
 
     import torch
-    from paper_2504_14152_amd import fgmp, synth
+    from paper_2504_14152_amd import build as fgmp_build, fgmp, synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = "cuda"
     fgmp.lib()  # fail loudly if the HIP library is missing
+    traffic_bytes = traffic_from_profile()
 
     def dev_bf16(x32):
         bits = synth.f32_to_bf16_bits(x32)
@@ -157,13 +171,15 @@ def main() -> int:
     for ea, eb in pairs:      # torch creates the HIP event on first use
         ea.record()
         eb.record()
-    for _ in range(10):
-        step()
-    for ea, eb in pairs:
-        fgmp.selftest_time_gemm_kernel(ea, eb)
-        step()
-    fgmp.selftest_time_gemm_kernel(None, None)
-    torch.cuda.synchronize()
+    # (the shipped library has no hook: the same sources built with FGMP_MEASUREMENT_HOOKS serve here)
+    with fgmp.use_library(fgmp_build.lib_path("hooks")):
+        for _ in range(10):
+            step()
+        for ea, eb in pairs:
+            fgmp.selftest_time_gemm_kernel(ea, eb)
+            step()
+        fgmp.selftest_time_gemm_kernel(None, None)
+        torch.cuda.synchronize()
     per_launch = sorted(ea.elapsed_time(eb) for ea, eb in pairs)
     ms_kernel = max(sum(per_launch) / len(per_launch), 1e-6)
     achieved = flops / (ms_kernel * 1e-3) / 1e12
@@ -194,7 +210,7 @@ def main() -> int:
     reference = {"mfma_loop_TFLOPs": round(mfma_loop_tflops, 1), "device_copy_GBps": round(copy_gbps, 1)}
     roofline = {"bound": "mfma", "kernel": "gemm_mixed_kernel", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
-                "traffic": GEMM_KERNEL_HBM_BYTES, "ms_per_launch": round(ms_kernel, 4),
+                "traffic": traffic_bytes, "ms_per_launch": round(ms_kernel, 4),
                 "ms_per_launch_median": round(per_launch[len(per_launch) // 2], 4),
                 "ms_step_minus_quantizer": round(ms_step - ms_quant16, 4), "ms_quantize_to_f16": round(ms_quant16, 4),
                 "frac_of_measured_mfma_loop": round(achieved / mfma_loop_tflops, 4),
@@ -519,7 +535,7 @@ def main() -> int:
         del pool
         extra["qkv_between_decode_and_prefill_hbm_cold"] = small
 
-    if args.sweep:
+    if not args.no_sweep and not args.no_extra:
         sw_res = {}
         for frac in (0.0, 0.1, 0.2, 0.3, 1.0):
             sw_res[f"fp8_{int(frac * 100)}pct"] = prefill_case(2048, 8192, 57344, frac, frac, "normal", 60)

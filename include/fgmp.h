@@ -318,7 +318,9 @@ fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *
 
 /*
  * Measurement hook: the duration of the prefill GEMM kernel inside a fused
- * call.  While a pair of HIP events (hipEvent_t, created by the caller with
+ * call.  Only libraries built with FGMP_MEASUREMENT_HOOKS have it (the
+ * benchmark's libfgmp_hooks.so); in the shipped library setting a pair returns
+ * FGMP_ERR_UNSUPPORTED and the launcher records nothing.  While a pair of HIP events (hipEvent_t, created by the caller with
  * timing enabled) is set, every launch of that kernel records `ev_start` on
  * its stream immediately before the launch and `ev_stop` immediately after;
  * the caller synchronizes and reads hipEventElapsedTime.  Two null pointers

@@ -260,8 +260,9 @@ fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *
 fgmp_status_t fgmp_selftest_time_gemm_kernel(void *ev_start, void *ev_stop)
 {
     if ((ev_start == nullptr) != (ev_stop == nullptr)) return FGMP_ERR_INVALID_ARG;
-    set_gemm_kernel_events(static_cast<hipEvent_t>(ev_start), static_cast<hipEvent_t>(ev_stop));
-    return FGMP_OK;
+    return set_gemm_kernel_events(static_cast<hipEvent_t>(ev_start), static_cast<hipEvent_t>(ev_stop))
+               ? FGMP_OK
+               : (ev_start == nullptr ? FGMP_OK : FGMP_ERR_UNSUPPORTED);   // clearing "nothing" always works
 }
 
 }  // extern "C"

@@ -227,15 +227,20 @@ static GemmWorkspace gemm_ws_layout(int64_t M, int64_t N, int64_t K)
     return w;
 }
 
-// FGMP_PREFILL_KERNEL=dense selects the two-pass path (both operands expanded to FP16 in the
-// workspace, then a plain FP16 kernel); the default decodes the weights inside the MFMA kernel.
+// The prefill kernel decodes the weights inside the MFMA kernel.  Builds with FGMP_MEASUREMENT_HOOKS
+// (never the shipped library) can select the two-pass path instead -- both operands expanded to FP16
+// in the workspace, then a plain FP16 kernel -- with FGMP_PREFILL_KERNEL=dense in the environment.
 static bool prefill_decodes_in_kernel()
 {
+#ifdef FGMP_MEASUREMENT_HOOKS
     static const bool in_kernel = [] {
         const char *e = getenv("FGMP_PREFILL_KERNEL");
         return !(e && e[0] == 'd');
     }();
     return in_kernel;
+#else
+    return true;
+#endif
 }
 
 // The MFMA kernel that decodes the weights itself addresses them with 32-bit buffer offsets; larger

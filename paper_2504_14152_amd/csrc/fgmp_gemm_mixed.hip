@@ -71,20 +71,27 @@ __device__ __forceinline__ void load_b16(uint32_t &d, __amdgpu_buffer_rsrc_t r, 
     asm volatile("buffer_load_ushort %0, %1, %2, %3 offen" : "=v"(d) : "v"(voff), "s"(r), "s"(soff));
 }
 // Wait until at most kPending loads are outstanding; the named registers count as written here, so
-// no use of them can move above the wait.
+// no use of them can move above the wait.  A build with FGMP_FULL_WAITS waits for every load instead
+// (kPending = 0 everywhere): same instructions, same summation order, no counting to get wrong -- the
+// library a test compares this one with, bit for bit.
+#ifdef FGMP_FULL_WAITS
+constexpr int pending(int) { return 0; }
+#else
+constexpr int pending(int n) { return n; }
+#endif
 template <int kPending, int kBPT> __device__ __forceinline__ void wait_loaded(LRegs<kBPT> &b)
 {
-    if constexpr (kBPT == 2) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b.l[0]) : "n"(kPending));
-    else asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b.l[0]), "+v"(b.l[1]) : "n"(kPending));
+    if constexpr (kBPT == 2) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b.l[0]) : "n"(pending(kPending)));
+    else asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b.l[0]), "+v"(b.l[1]) : "n"(pending(kPending)));
 }
 template <int kPending> __device__ __forceinline__ void wait_loaded(MetaRegs &b)
 {
-    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b.s), "+v"(b.m), "+v"(b.t) : "n"(kPending));
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b.s), "+v"(b.m), "+v"(b.t) : "n"(pending(kPending)));
 }
 template <int kPending, int kBPT> __device__ __forceinline__ void wait_loaded(u32x2_t (&h)[kBPT])
 {
-    if constexpr (kBPT == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(h[0]), "+v"(h[1]) : "n"(kPending));
-    else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]) : "n"(kPending));
+    if constexpr (kBPT == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(h[0]), "+v"(h[1]) : "n"(pending(kPending)));
+    else asm volatile("s_waitcnt vmcnt(%4)" : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]) : "n"(pending(kPending)));
 }
 
 // kPackOut: instead of storing FP32 results, the epilogue scores and quantizes them block by block (16
@@ -305,7 +312,7 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         order_phase<kReads, kMfma, 0>();
         // LDS traffic of this wave done (lgkmcnt 0) and its A loads landed: they are older than this
         // iteration's kBLoads register loads, which may stay in flight (vmcnt kBLoads)
-        __builtin_amdgcn_s_waitcnt(0x0070 | kBLoads);
+        __builtin_amdgcn_s_waitcnt(0x0070 | pending(kBLoads));
         __syncthreads();
         issue_a(kt + 2 < nk ? kt + 2 : nk - 1, st);
         read_frags(st ^ 1, 0, fa[0], fb[0]);
@@ -560,18 +567,27 @@ SplitTail plan_split_tail(int64_t n_tiles, int nk, void *region)
     return sp;
 }
 
-static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;   // measurement hook
-void set_gemm_kernel_events(hipEvent_t start, hipEvent_t stop)
+// Measurement hook (only in builds with FGMP_MEASUREMENT_HOOKS; the shipped launcher records nothing):
+// a pair of events recorded around every launch of the kernel.
+#ifdef FGMP_MEASUREMENT_HOOKS
+static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+bool set_gemm_kernel_events(hipEvent_t start, hipEvent_t stop)
 {
     g_ev_start = start;
     g_ev_stop = stop;
+    return true;
 }
+#else
+bool set_gemm_kernel_events(hipEvent_t, hipEvent_t) { return false; }
+#endif
 
 void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, const PackedLayout &lw, float *Y,
                        int64_t ldy, int64_t M, int64_t N, int64_t n_tm, int64_t n_tn, const PackedHeader *ha,
                        hipStream_t st, const SplitTail &sp, const PackOut *pack_out)
 {
+#ifdef FGMP_MEASUREMENT_HOOKS
     if (g_ev_start) (void)hipEventRecord(g_ev_start, st);
+#endif
     const unsigned grid = (unsigned)(sp.n_whole + sp.n_parts * sp.n_split);
 #ifndef FGMP_MIXED_WM
 #define FGMP_MIXED_WM 2
@@ -590,7 +606,9 @@ void launch_gemm_mixed(const _Float16 *a16, int64_t ld, const PackedView &W, con
         hipLaunchKernelGGL((gemm_mixed_kernel<FGMP_MIXED_WM, FGMP_MIXED_WN, false, false>), dim3(grid),
                            dim3(kThreads), 0, st, a16, ld, W, lw, (int)(ld / kBK), Y, ldy, M, N, n_tm, n_tn, ha,
                            PackOut{}, sp);
+#ifdef FGMP_MEASUREMENT_HOOKS
     if (g_ev_stop) (void)hipEventRecord(g_ev_stop, st);
+#endif
 }
 
 }  // namespace fgmp

@@ -100,7 +100,8 @@ fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *m
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);
 fgmp_status_t selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, hipStream_t st);
-// events recorded around every launch of the prefill GEMM kernel (both null: none)
-void set_gemm_kernel_events(hipEvent_t start, hipEvent_t stop);
+// events recorded around every launch of the prefill GEMM kernel (both null: none); false when the
+// library was built without the measurement hooks
+bool set_gemm_kernel_events(hipEvent_t start, hipEvent_t stop);
 
 }  // namespace fgmp

@@ -28,16 +28,59 @@ class _PackedInfo(ctypes.Structure):
                 ("n_fp8_blocks", ctypes.c_int64), ("bytes_used", ctypes.c_int64)]
 
 
+def _library_file() -> str:
+    """The shared library to load: FGMP_LIB_PATH (a library built elsewhere, or one of the build's
+    variants) or the in-tree libfgmp.so.  A missing in-tree library is built; one that is older than
+    any of its sources is rebuilt when a compiler is at hand and refused otherwise, so that no test or
+    benchmark result can belong to old code without notice."""
+    path = os.environ.get("FGMP_LIB_PATH")
+    if path:
+        if not os.path.exists(path):
+            raise FgmpError(f"FGMP_LIB_PATH={path} does not exist")
+        return path
+    path = _build.lib_path()
+    if _build.is_stale(path):
+        have_compiler = os.path.exists(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"))
+        if have_compiler:
+            _build.build()
+        elif not os.path.exists(path):
+            raise FgmpError(f"{path} is missing and there is no hipcc to build it")
+        else:
+            raise FgmpError(f"{path} is older than its sources and there is no hipcc to rebuild it")
+    return path
+
+
 def lib() -> ctypes.CDLL:
-    """Load libfgmp.so (building it first only if it does not exist)."""
+    """Load libfgmp.so (see _library_file) and declare its entry points."""
     global _lib
     if _lib is not None:
         return _lib
-    path = os.environ.get("FGMP_LIB_PATH") or _build.lib_path()   # override: a library built elsewhere
-    if not os.path.exists(path):
-        if path != _build.lib_path():
-            raise FgmpError(f"FGMP_LIB_PATH={path} does not exist")
-        _build.build()
+    _lib = _load(_library_file())
+    return _lib
+
+
+class use_library:
+    """Context manager: route this module's calls to another build of the library (a variant from
+    build.lib_path(variant)) for the duration of the block.  For tests and measurements."""
+
+    def __init__(self, path: str):
+        if not os.path.exists(path):
+            raise FgmpError(f"{path} does not exist")
+        self._other = _load(path)
+
+    def __enter__(self):
+        global _lib
+        lib()
+        self._saved, _lib = _lib, self._other
+        return self._other
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self._saved
+        return False
+
+
+def _load(path: str) -> ctypes.CDLL:
     L = ctypes.CDLL(path)
     vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     L.fgmp_version.restype = ctypes.c_char_p
@@ -95,7 +138,6 @@ def lib() -> ctypes.CDLL:
     L.fgmp_selftest_mfma_rate.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp]
     L.fgmp_selftest_time_gemm_kernel.restype = ctypes.c_int
     L.fgmp_selftest_time_gemm_kernel.argtypes = [vp, vp]
-    _lib = L
     return L
 
 

@@ -119,3 +119,26 @@ def exact_sum_operand(rows: int, K: int, seed: int, tensor_id: int, fp8_block_fr
     v = np.where(kind8, b, a) * sign * np.exp2(j).astype(np.float32)
     return v.reshape(rows, K).astype(np.float32)
 
+
+
+def exact_sum_operand_long_k(rows: int, K: int, seed: int, tensor_id: int, fp8_block_fraction: float = 0.2) -> np.ndarray:
+    """Like exact_sum_operand, for long dot products: every value is a multiple of 2**-3 of magnitude <= 3,
+    so a product of two such tensors is a sum of multiples of 2**-6 bounded by 9 K -- exact in fp32 in any
+    summation order up to K = 2**16 / 9 * 2**2 (|sum| * 64 < 2**24 holds for K <= 29127).  Each block is scaled by
+    2**j, j in {-1, 0}; most blocks hold values from {0, .25, .5, .75, 1, 1.5, 2, 3} * 2**j with 3 * 2**j
+    present (a 4-bit block with block scale 2**(j-1) when the tensor scale is 1), the others multiples of
+    2**j / 4 up to 2.75 * 2**j with 2.75 * 2**j and 0.25 * 2**j present (exact as 8-bit floating point, not as a 4-bit block)."""
+    rng = rng_for(seed, tensor_id)
+    nb = K // 16
+    grid4 = np.array([0.0, 0.25, 0.5, 0.75, 1.0, 1.5, 2.0, 3.0], dtype=np.float32)
+    j = rng.integers(-1, 1, size=(rows, nb, 1)).astype(np.float32)
+    sign = rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=(rows, nb, 16))
+    a = grid4[rng.integers(0, 8, size=(rows, nb, 16))]
+    pos = rng.integers(0, 16, size=(rows, nb))
+    np.put_along_axis(a, pos[..., None], np.float32(3.0), axis=2)
+    b = rng.integers(0, 12, size=(rows, nb, 16)).astype(np.float32) / np.float32(4.0)
+    b[..., 0] = np.float32(2.75)
+    b[..., 1] = np.float32(0.25)
+    kind8 = rng.random(size=(rows, nb, 1)) < fp8_block_fraction
+    v = np.where(kind8, b, a) * sign * np.exp2(j).astype(np.float32)
+    return v.reshape(rows, K).astype(np.float32)

@@ -503,6 +503,54 @@ def test_fused_gated_packed_output_matches_oracle(M, K, N):
     assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(a), fgmp.unpack_canonical(b)))
 
 
+def test_packed_output_epilogues_match_oracle_at_full_k():
+    """Both quantizing epilogues against the ORACLE at 4352 x 4096 x 4096: 256 whole tiles and 16 tiles
+    computed in four parts along K in one launch, 64 K-steps (ten turns of the kernel's six-step register
+    rotation plus a remainder).  The operands are built so that every partial sum of the product is an
+    exact FP32 number in any order (multiples of 1/64 well below 2^24 / 64), so the FP32 results the
+    epilogue quantizes are the oracle's results bit for bit, and so must be every code, scale, decision
+    and score -- without and with the gated activation."""
+    M, K, N = 4352, 4096, 4096
+    _say(f"packed-output epilogues vs oracle at {M}x{K}x{N}")
+    x = synth.exact_sum_operand_long_k(M, K, 71, 1)
+    w = synth.exact_sum_operand_long_k(N, K, 71, 2)
+    ones = np.ones(K, dtype=np.float32)
+    qw = orc.quantize(w, ones, 0.0, 1.0)
+    qx = orc.quantize(x, ones, 0.0, 1.0)
+    ax, aw = orc.dequantize(qx["codes"], qx["scales"], qx["mask"]), orc.dequantize(qw["codes"], qw["scales"], qw["mask"])
+    assert np.array_equal(ax, x.astype(np.float64)) and np.array_equal(aw, w.astype(np.float64))
+    assert 0.1 < qx["mask"].mean() < 0.35 and 0.1 < qw["mask"].mean() < 0.35
+    y64, _ = orc.gemm(ax, 1.0, aw, 1.0)
+    del ax, aw
+    y32 = y64.astype(np.float32)
+    assert np.array_equal(y32.astype(np.float64), y64) and np.abs(y64).max() * 64 < 2 ** 24 / 16
+    del y64
+    xd, wd, od = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV), torch.from_numpy(ones).to(DEV)
+    pW = fgmp.quantize_weights(wd, od, 0.0, 1.0)
+    Y = fgmp.quant_gemm_fused(xd, od, 0.0, 1.0, pW)
+    assert np.array_equal(Y.cpu().numpy(), y32)
+    del Y
+    # plain epilogue
+    f_n = synth.fisher_per_channel(N, 71, 3)
+    s_y = float(np.float32(np.abs(y32).max()) / np.float32(448.0))
+    T_y = orc.threshold(orc.quantize(y32, f_n, np.inf, s_y)["scores"], 0.2)
+    want = orc.quantize(y32, f_n, T_y, s_y)
+    pY, scores = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_n).to(DEV), T_y, s_y,
+                                                  want_scores=True)
+    _assert_quant_equal(pY, scores, want, "packed output at full K")
+    assert fgmp.packed_info(pY)["n_fp8_blocks"] == int(want["mask"].sum())
+    del pY, scores, want
+    # gated epilogue
+    h32 = orc.gate_columns(y32)
+    f_h = synth.fisher_per_channel(N // 2, 71, 4)
+    s_h = float(np.float32(np.abs(h32).max()) / np.float32(448.0))
+    T_h = orc.threshold(orc.quantize(h32, f_h, np.inf, s_h)["scores"], 0.2)
+    want = orc.quantize(h32, f_h, T_h, s_h)
+    pH, scores = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_h).to(DEV), T_h, s_h,
+                                                  want_scores=True, epilogue=fgmp.EPILOGUE_SILU_GATE)
+    _assert_quant_equal(pH, scores, want, "gated packed output at full K")
+
+
 @pytest.mark.parametrize("M,K,N", [(200, 512, 320), (4352, 256, 4096), (9, 1024, 192)])
 def test_gated_packed_output_on_random_inputs_is_consistent(M, K, N):
     """On ordinary inputs: the gated epilogue equals the oracle's gate applied to the very FP32 results
@@ -553,6 +601,9 @@ def test_argument_errors():
 
 # ------------------------------------------------------------------ GEMM
 
+ORACLE_THRESHOLD_LIMIT = 64 * 1024 * 1024
+
+
 def _quantized_pair(M, K, N, seed, p, kind="normal", per_elem_w=True):
     x = synth.activations(M, K, seed, 1, kind=kind)
     w = synth.weights(N, K, seed, 2)
@@ -562,10 +613,16 @@ def _quantized_pair(M, K, N, seed, p, kind="normal", per_elem_w=True):
     wd, wref = _to_dev_bf16(w)
     sx, sw = float(synth.default_tensor_scale(xref)), float(synth.default_tensor_scale(wref))
     fxd, fwd = torch.from_numpy(fx).to(DEV), torch.from_numpy(fw).to(DEV)
-    # thresholds from the library's own scores (bit-equal to the oracle's, tested above)
-    _, sxs = fgmp.quantize_activations(xd, fxd, np.inf, sx, want_scores=True)
-    _, sws = fgmp.quantize_weights(wd, fwd, np.inf, sw, want_scores=True)
-    Tx, Tw = fgmp.threshold_for_fraction(sxs, p), fgmp.threshold_for_fraction(sws, p)
+    # thresholds from the ORACLE's scores (so that a GEMM test also notices a score regression); tensors
+    # beyond 64 M elements take the library's scores, which other tests show bit-equal to the oracle's
+    if M * K <= ORACLE_THRESHOLD_LIMIT:
+        Tx = orc.threshold(orc.quantize(xref, fx, np.inf, sx)["scores"], p)
+    else:
+        Tx = fgmp.threshold_for_fraction(fgmp.quantize_activations(xd, fxd, np.inf, sx, want_scores=True)[1], p)
+    if N * K <= ORACLE_THRESHOLD_LIMIT:
+        Tw = orc.threshold(orc.quantize(wref, fw, np.inf, sw)["scores"], p)
+    else:
+        Tw = fgmp.threshold_for_fraction(fgmp.quantize_weights(wd, fwd, np.inf, sw, want_scores=True)[1], p)
     pX = fgmp.quantize_activations(xd, fxd, Tx, sx)
     pW = fgmp.quantize_weights(wd, fwd, Tw, sw)
     return dict(xd=xd, xref=xref, wref=wref, fx=fx, fw=fw, fxd=fxd, sx=sx, sw=sw, Tx=Tx, Tw=Tw, pX=pX, pW=pW)
@@ -701,12 +758,15 @@ def test_gemm_llama_fc1_prefill_sampled():
     assert torch.equal(Yf, fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"]))
 
 
-def test_gemm_llama70b_fc1_shape_sampled():
+@pytest.mark.parametrize("p", [0.1, 0.0, 1.0])
+def test_gemm_llama70b_fc1_shape_sampled(p):
     """The sweep's shape (configs[4]: K 8192, N 57344, M 2048; 470 M weights, 1792 output tiles) and a
-    decode step on the same weights.  The weights are drawn on the device (seeded); the oracle quantizes
+    decode step on the same weights, at the sweep's end points too: no FP8 block at all, and every block
+    FP8 (the compact upper-half plane is then eight times larger, and a decode step finds more FP8 blocks
+    per K range than it stages).  The weights are drawn on the device (seeded); the oracle quantizes
     the sampled rows of X and W itself from the very same bf16 values."""
-    M, K, N, p = 2048, 8192, 57344, 0.1
-    _say("gemm 70B fc1 2048x8192x57344")
+    M, K, N = 2048, 8192, 57344
+    _say(f"gemm 70B fc1 2048x8192x57344 p={p}")
     gen = torch.Generator(device=DEV)
     gen.manual_seed(70)
     wd = torch.empty((N, K), dtype=torch.bfloat16, device=DEV).normal_(0.0, 0.02, generator=gen)
@@ -778,6 +838,28 @@ def test_gemm_decode_shapes(M, K, N, p):
     assert torch.equal(Y, Yf)
 
 
+@pytest.mark.parametrize("name", ["qkv", "fc1"])
+def test_gemm_decode_llama_shapes_at_full_size(name):
+    """The benchmark's decode steps at their real sizes and 10% FP8 on both sides: M = 1, 8 and 32 rows
+    against the fused QKV weights (12288 x 4096) and the FC1 weights (22016 x 4096).  Every 7th output
+    column at full K against the oracle; fused call, packed-activation call and a repeated call agree bit
+    for bit."""
+    K, N = synth.LLAMA2_7B[name]
+    _say(f"decode full size {name}: N={N} K={K}")
+    c = _quantized_pair(32, K, N, 13, 0.1, per_elem_w=False)
+    cols = np.arange(0, N, 7)
+    cols[-1] = N - 1
+    for M in (1, 8, 32):
+        xm = c["xd"][:M].contiguous()
+        Yf = fgmp.quant_gemm_fused(xm, c["fxd"], c["Tx"], c["sx"], c["pW"])
+        cm = dict(c, xref=c["xref"][:M])
+        _check_gemm(cm, Yf, np.arange(M), cols, label=f"decode {name} M={M}")
+        assert torch.isfinite(Yf).all()
+        pXm = fgmp.quantize_activations(xm, c["fxd"], c["Tx"], c["sx"])
+        assert torch.equal(Yf, fgmp.gemm(pXm, c["pW"]))
+        assert torch.equal(Yf, fgmp.quant_gemm_fused(xm, c["fxd"], c["Tx"], c["sx"], c["pW"]))
+
+
 @pytest.mark.parametrize("M,K,N,p", [(4, 1024, 200, 0.1), (24, 2048, 136, 0.3), (300, 512, 264, 0.1),
                                      (8, 256, 72, 0.0), (300, 256, 72, 0.0)])
 def test_compact_weights_relocated_to_bytes_used(M, K, N, p):
@@ -804,8 +886,8 @@ def test_compact_weights_relocated_to_bytes_used(M, K, N, p):
 
 
 def test_gemm_two_pass_path_in_subprocess():
-    """The alternative prefill path (both operands expanded to FP16 first) is chosen
-    once per process by FGMP_PREFILL_KERNEL=dense; check it in a child process."""
+    """The alternative prefill path (both operands expanded to FP16 first) exists only in the build with
+    measurement hooks, where FGMP_PREFILL_KERNEL=dense chooses it once per process; check it in a child process."""
     import os
     import subprocess
     import sys
@@ -818,7 +900,8 @@ def test_gemm_two_pass_path_in_subprocess():
         "t._check_gemm(c, Y, label='two-pass')\n"
         "print('two-pass ok')\n"
     ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, FGMP_PREFILL_KERNEL="dense")
+    from paper_2504_14152_amd import build
+    env = dict(os.environ, FGMP_PREFILL_KERNEL="dense", FGMP_LIB_PATH=build.lib_path("hooks"))
     res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110)
     assert res.returncode == 0 and "two-pass ok" in res.stdout, res.stdout + res.stderr
 
@@ -833,25 +916,58 @@ def test_mfma_rate_reference_runs():
 
 
 def test_gemm_kernel_timing_hook():
-    """The measurement hook brackets the prefill GEMM kernel with the caller's events; cleared, it records nothing."""
+    """The measurement hook (only in the build variant with hooks) brackets the prefill GEMM kernel with the
+    caller's events; cleared, it records nothing; the shipped library has no hook and says so."""
+    from paper_2504_14152_amd import build
     c = _quantized_pair(300, 512, 264, 5, 0.1, per_elem_w=False)
     ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ea.record()
     eb.record()
     torch.cuda.synchronize()
-    fgmp.selftest_time_gemm_kernel(ea, eb)
-    try:
-        Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
-    finally:
-        fgmp.selftest_time_gemm_kernel(None, None)
-    torch.cuda.synchronize()
-    ms = ea.elapsed_time(eb)
-    assert 0.0 < ms < 50.0
-    _check_gemm(c, Y, label="timed launch")
-    # with the hook cleared the events keep their timestamps
-    fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
-    torch.cuda.synchronize()
-    assert ea.elapsed_time(eb) == ms
+    with pytest.raises(fgmp.FgmpError):
+        fgmp.selftest_time_gemm_kernel(ea, eb)
+    fgmp.selftest_time_gemm_kernel(None, None)
+    Y_shipped = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    with fgmp.use_library(build.lib_path("hooks")):
+        fgmp.selftest_time_gemm_kernel(ea, eb)
+        try:
+            Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+        finally:
+            fgmp.selftest_time_gemm_kernel(None, None)
+        torch.cuda.synchronize()
+        ms = ea.elapsed_time(eb)
+        assert 0.0 < ms < 50.0
+        _check_gemm(c, Y, label="timed launch")
+        assert torch.equal(Y, Y_shipped)
+        # with the hook cleared the events keep their timestamps
+        fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+        torch.cuda.synchronize()
+        assert ea.elapsed_time(eb) == ms
+
+
+@pytest.mark.parametrize("M,K,N", [(4096, 4096, 12288), (4096, 4096, 22016), (4352, 512, 4096), (300, 1040, 264)])
+def test_hand_counted_waits_against_full_waits(M, K, N):
+    """Runtime guard for the prefill kernel's hand-counted `s_waitcnt vmcnt(N)`: a second build of the same
+    sources in which every such wait is a full one (nothing to miscount) must give the same Y bit for bit
+    -- same instructions, same summation order, so any difference is a register read before its load
+    landed.  QKV and FC1 at full size (FC1 with tiles split in two along K), a shape with four-part split
+    tiles, and a ragged one; whatever the compiler made of the loop."""
+    from paper_2504_14152_amd import build
+    _say(f"counted waits vs full waits {M}x{K}x{N}")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(90 + N)
+    wd = torch.empty((N, K), dtype=torch.bfloat16, device=DEV).normal_(0.0, 0.02, generator=gen)
+    xd, xref = _to_dev_bf16(synth.activations(M, K, 90, 1))
+    fxd = torch.from_numpy(synth.fisher_per_channel(K, 90, 3)).to(DEV)
+    sx, sw = float(synth.default_tensor_scale(xref)), float(wd.abs().max().float()) / 448.0
+    _, sws = fgmp.quantize_weights(wd, fxd, np.inf, sw, want_scores=True)
+    pW = fgmp.quantize_weights(wd, fxd, fgmp.threshold_for_fraction(sws, 0.1), sw)
+    del sws, wd
+    Tx = fgmp.threshold_for_fraction(fgmp.quantize_activations(xd, fxd, np.inf, sx, want_scores=True)[1], 0.1)
+    Y = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW)
+    with fgmp.use_library(build.lib_path("fullwait")):
+        Y_full = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW)
+    assert torch.isfinite(Y).all() and torch.equal(Y, Y_full)
 
 
 @pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (300, 512, 520), (70, 1024, 512)])
