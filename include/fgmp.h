@@ -153,6 +153,28 @@ fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, i
                                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * fgmp_quant_gemm_fused for callers that cannot allocate device memory and have no workspace to
+ * hand over -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc:
+ * the scratch memory (the quantized activations as FP16 values, partial sums and arrival counters
+ * of products computed in several parts) lives in a static device array of
+ * FGMP_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.  The
+ * call allocates nothing and frees nothing; same arguments, results (bit for bit) and errors as
+ * fgmp_quant_gemm_fused, without the workspace.
+ *   limit      fgmp_workspace_bytes(M, N, K) <= FGMP_STATIC_SCRATCH_BYTES, else
+ *              FGMP_ERR_BUFFER_TOO_SMALL and nothing is launched (all decode shapes, M <= 32, of the
+ *              Llama-2-7B linears fit; prefill shapes generally do not)
+ *   sharing    every call on a GPU uses that GPU's one array: calls that overlap in time on the
+ *              same GPU (different streams or threads) race; calls on one stream are ordered
+ *   first call on a device looks up the array's address (hipGetSymbolAddress); make that call
+ *              outside a stream capture
+ */
+#define FGMP_STATIC_SCRATCH_BYTES (16 * 1024 * 1024)
+fgmp_status_t fgmp_quant_gemm_fused_static_scratch(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K,
+                                                   int64_t ldx, const float *fisher_k, float threshold,
+                                                   float scale_x, const void *packed_W, int64_t N, float *Y,
+                                                   int64_t ldy, void *stream);
+
+/*
  * The three calls above with the score selected by `score_mode` (Sec. 3.1, Eq. 8; Sec. 3.4);
  * all other arguments, outputs and errors as the plain calls.  FGMP_ERR_INVALID_ARG for an unknown mode.
  */

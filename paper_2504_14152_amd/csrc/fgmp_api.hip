@@ -1,5 +1,6 @@
 // C ABI of libfgmp: argument checks and dispatch.  See include/fgmp.h.
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "fgmp_internal.hpp"
@@ -7,6 +8,27 @@
 using namespace fgmp;
 
 static inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+// Scratch memory of fgmp_quant_gemm_fused_static_scratch: one array per GPU the library runs on, held
+// until the process ends.  The name below is a host-side stand-in, not a device address: host code
+// reaches the array only through the address hipGetSymbolAddress returns, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[FGMP_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+static fgmp_status_t static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FGMP_ERR_HIP;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        // (two threads may both look it up: they get the same address)
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FGMP_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return FGMP_OK;
+}
 
 extern "C" {
 
@@ -55,6 +77,22 @@ fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, i
 {
     return quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Y, ldy, workspace,
                       workspace_bytes, as_stream(stream));
+}
+
+fgmp_status_t fgmp_quant_gemm_fused_static_scratch(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                                   const float *fisher_k, float threshold, float scale_x,
+                                                   const void *packed_W, int64_t N, float *Y, int64_t ldy,
+                                                   void *stream)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
+    // the size check comes first: a product that does not fit must not touch the array
+    if (gemm_workspace_bytes(M, N, K) > (size_t)FGMP_STATIC_SCRATCH_BYTES) return FGMP_ERR_BUFFER_TOO_SMALL;
+    void *ws = nullptr;
+    const fgmp_status_t rc = static_scratch(&ws);
+    if (rc != FGMP_OK) return rc;
+    return quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Y, ldy, ws,
+                      (size_t)FGMP_STATIC_SCRATCH_BYTES, as_stream(stream));
 }
 
 fgmp_status_t fgmp_quantize_weights_ex(const void *W, fgmp_dtype_t dt, int64_t N, int64_t K, int64_t ldw,

@@ -117,6 +117,8 @@ def _load(path: str) -> ctypes.CDLL:
     L.fgmp_quant_gemm_fused.restype = ctypes.c_int
     L.fgmp_quant_gemm_fused.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, vp, i64,
                                         vp, sz, vp]
+    L.fgmp_quant_gemm_fused_static_scratch.restype = ctypes.c_int
+    L.fgmp_quant_gemm_fused_static_scratch.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, f32, f32, vp, i64, vp, i64, vp]
     L.fgmp_unpack_canonical.restype = ctypes.c_int
     L.fgmp_unpack_canonical.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     L.fgmp_dequantize_f16.restype = ctypes.c_int
@@ -287,6 +289,24 @@ def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, 
                                             N, _ptr(Y), Y.stride(0), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "fgmp_quant_gemm_fused")
     return Y
+
+
+STATIC_SCRATCH_BYTES = 16 * 1024 * 1024   # FGMP_STATIC_SCRATCH_BYTES
+
+
+def quant_gemm_fused_static_scratch(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, scale_x: float,
+                                    pW: Packed, out: torch.Tensor) -> torch.Tensor:
+    """quant_gemm_fused without a workspace: the library's static scratch array serves (small products
+    only).  `out` is required: the binding allocates nothing either."""
+    _require_cuda(X, fisher_k, out)
+    M, K = X.shape
+    if K != pW.K:
+        raise FgmpError("K mismatch")
+    rc = lib().fgmp_quant_gemm_fused_static_scratch(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
+                                                    float(threshold), float(scale_x), _ptr(pW.buf), pW.rows,
+                                                    _ptr(out), out.stride(0), _stream())
+    _check(rc, "fgmp_quant_gemm_fused_static_scratch")
+    return out
 
 
 def quant_gemm_fused_packed_out(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, scale_x: float,
