@@ -18,10 +18,13 @@
 //   plane T   one uint32 per tile: index (in 8-byte entries) of the tile's
 //             first entry in plane H.
 //   plane H   8 bytes per FP8 block: its last 8 E4M3 bytes.  "strided"
-//             tensors (activations, written in one pass) give every tile room
-//             for 64 entries, T[t] = 64 t; "compact" tensors (weights, packed
-//             offline) store the entries back to back, so the tensor occupies
-//             9 B per FP4 block and 16 B per FP8 block plus tables.
+//             tensors (activations, written in one pass) reserve room for 64
+//             entries per tile; where a tile's entries start is the writer's
+//             choice (T[t] = 64 t, or the tiles one wave visits appended one
+//             after the other) and readers only go by T[t].  "compact" tensors
+//             (weights, packed offline) store the entries back to back in tile
+//             order, so the tensor occupies 9 B per FP4 block and 16 B per FP8
+//             block plus tables.
 //   Slots outside the tensor (row >= rows or K-block >= K/16) hold FP4 zeros.
 //
 // A 256-byte header precedes the planes; every plane starts 256-byte aligned.

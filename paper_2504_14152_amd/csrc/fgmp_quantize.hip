@@ -8,11 +8,15 @@
 //   t_i = ((x_i - xh_i) * (x_i - xh_i)) * F_i                        (Eq. 2, Eq. 6)
 //   score = balanced pairwise tree over t_0..t_15 (adjacent pairs first)
 //   FP8 iff score > T (Sec. 4.2); FP8 codes c_i = E4M3(x_i * (1 / S))  (Sec. 5.1)
+#include <algorithm>
+
 #include "fgmp_internal.hpp"
 #include "fgmp_quant_block.hpp"
 
 namespace fgmp {
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 struct QuantParams {
     const void *X;
@@ -248,6 +252,239 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p)
     process(rt0 + 4 * (int64_t)(n_it - 1), cur);
 }
 
+// ---------------------------------------------------------------------------
+// The activation hot path (Sec. 4.2) once more, trimmed: same arithmetic, result for result, as
+// quantize_kernel (NVFP4-error score, one sensitivity per channel, dynamic-max scale).
+//   * d = value(sc) * S and 1 / d depend only on the scale code: a table of 127 {d, 1/d} pairs per
+//     workgroup (LDS) replaces the decode, the multiply and the division of every block;
+//   * u = amax / (6 S) is one multiply by the correctly rounded reciprocal r and one correction step,
+//     q1 = fma(fma(-q0, 6S, amax), r, q0): the correctly rounded quotient (q0 is within one unit of it and
+//     the residual is exact; magnitudes near the ends of the FP32 range, where that fails, take the plain
+//     division instead);
+//   * input through range-checked buffer loads: rows beyond the tensor read zeros without a select;
+//   * a workgroup's eight waves take eight consecutive K-tiles of one row-tile at a time (2 KB of every
+//     row, 4 KB of plane L, 512 B of plane S: contiguous), and workgroups that run at the same time cover
+//     whole rows; the launch is one resident set of workgroups that stride over the row-tiles, so a wave
+//     keeps its K-tile and the sensitivities stay in registers;
+//   * the 12 bytes of per-tile words are not stored tile by tile (those small stores alone cost 6% of the
+//     run time): the plane-M and plane-T words of eight row-tiles are gathered in LDS and leave as 64- and
+//     32-byte pieces;
+//   * the FP8 upper halves of the tiles a wave visits are appended to a region of plane H that belongs to
+//     the wave (see h_cnt below).
+// Tensors up to 4 GB (32-bit offsets).
+// ---------------------------------------------------------------------------
+constexpr int kQWaves = 8;    // waves per workgroup = consecutive K-tiles
+constexpr int kQBatch = 8;    // row-tiles between two writes of the gathered plane-M words
+constexpr int64_t kQMinTiles = 65536;   // smaller tensors do not fill the resident set for long enough: general kernel
+
+template <typename Tin, int kMode>
+__global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams p, uint32_t x_bytes, uint32_t out_bytes, int n_kg)
+{
+    static_assert(kMode == kModeStrided || kMode == kModeF16, "one-pass modes only");
+    constexpr int kVec = (int)(sizeof(RawBlock<Tin>) / sizeof(uint4));   // 16-byte loads per block
+    __shared__ float2 tbl[128];                                            // {d, 1/d} by scale code
+    __shared__ uint4 m_lds[kQBatch][kQWaves];                              // plane-M word and plane-T entry, [row-tile of the batch][K-tile]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = (int)blockIdx.x % n_kg;                 // the grid is a multiple of n_kg: the K group never changes
+    const int rt_first = (int)blockIdx.x / n_kg, rt_step = (int)gridDim.x / n_kg;
+    const uint32_t kt = (uint32_t)(kg * kQWaves + wave);
+    const uint32_t kb = kt * kTileBlocks + (lane & 7);
+    const bool kvalid = kb < (uint32_t)p.nb;               // (a whole wave may lie beyond K: it idles but keeps the barriers)
+    const int rloc = lane >> 3;
+    const float S = p.S, inv_S = 1.0f / S, S6 = 6.0f * S, r_S6 = 1.0f / S6;
+    if (tid < 128) {
+        const float d = e4m3_decode_int((uint32_t)tid) * S;
+        tbl[tid] = make_float2(d, tid != 0 ? 1.0f / d : 0.0f);
+    }
+    const __amdgpu_buffer_rsrc_t obuf =
+        __builtin_amdgcn_make_buffer_rsrc(p.out.hdr, 0, (int)out_bytes, 0x00020000);
+    const uint32_t off_L = (uint32_t)p.layout.off_L, off_S = (uint32_t)p.layout.off_S, off_M = (uint32_t)p.layout.off_M,
+                   off_T = (uint32_t)p.layout.off_T, off_H = (uint32_t)p.layout.off_H;
+    if (blockIdx.x == 0) {
+        if (tid == 0 && p.out.hdr != nullptr) write_header(p.out.hdr, p.layout, S, 0u);
+        for (int i = tid; i < p.zero_n; i += 64 * kQWaves) p.zero[i] = 0u;
+    }
+    float f[16];
+    if (kvalid) load16(p.fisher + kb * kBlock, f);
+    else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) f[i] = 0.0f;
+    }
+    __syncthreads();
+    if (rt_first >= (int)p.n_rt) return;
+    const int n_it = ((int)p.n_rt - rt_first + rt_step - 1) / rt_step;
+    // Plane H: the FP8 upper halves of all the tiles a wave visits go, in visiting order, into one region
+    // of the plane that belongs to the wave (64 entries per tile it owns: the worst case), so that the few
+    // entries of a tile continue where the previous tile's stopped instead of starting a 512-byte
+    // region of their own (those partial-line writes cost 7% of the run time at 10% FP8).  The regions
+    // of the waves with the same K-tile follow each other in the order of their first row-tile.
+    uint32_t h_cnt;
+    {
+        const uint32_t q = (uint32_t)p.n_rt / (uint32_t)rt_step, r = (uint32_t)p.n_rt % (uint32_t)rt_step, y = (uint32_t)rt_first;
+        h_cnt = (kt * (uint32_t)p.n_rt + y * q + (y < r ? y : r)) * kTileSlots;
+    }
+
+    // input: per-lane byte offset of the lane's block in the workgroup's first row-tile, advanced by rt_step
+    // row-tiles per iteration; rows beyond the tensor fall outside the buffer and read zeros; lanes
+    // beyond K stay parked outside it
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.X), 0, (int)x_bytes, 0x00020000);
+    const uint32_t row_bytes = (uint32_t)p.ldx * (uint32_t)sizeof(Tin);
+    uint32_t xoff = kvalid ? (uint32_t)(rt_first * kTileRows + rloc) * row_bytes + kb * (uint32_t)(kBlock * sizeof(Tin)) : 0xFFFFFF00u;
+    const uint32_t xstep = kvalid ? (uint32_t)rt_step * kTileRows * row_bytes : 0u;
+    auto load_block = [&](RawBlock<Tin> &r) {
+
+        // (a load past the last row-tile lies beyond the buffer -- zeros -- or is unused; offsets stay below 2^32
+        // for the tensors this kernel accepts plus one step, which the host checks)
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(xbuf, (int)xoff + 16 * i, 0, 0);
+            r.v[i] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+        xoff += xstep;
+    };
+
+    auto process = [&](int it, const RawBlock<Tin> &raw_in) {
+        const int rt = rt_first + it * rt_step;
+        float x[16];
+        widen(raw_in, x);
+        const float amax = block_amax(x);
+        // block scale: correctly rounded amax / (6 S)
+        float u = amax * r_S6;
+        // (outside [1e-30, 1e30) -- where a residual could lose bits or the product overflow -- the wave
+        // divides; zero is exact either way)
+        const bool odd_range = (amax < 1e-30f && amax != 0.0f) || !(u < 1e30f);
+        if (__builtin_expect(__ballot(odd_range) != 0ull, 0)) u = amax / S6;
+        else u = __builtin_fmaf(__builtin_fmaf(-u, S6, amax), r_S6, u);
+        const uint32_t sc = e4m3_encode_pair_hw(u, 0.0f) & 0xFFu;
+        const float2 dd = tbl[sc];
+        const float d = dd.x, inv_d = dd.y;
+        uint32_t q[2] = {0u, 0u};
+        float t[16];
+#define FGMP_ENC(W, B, I) q[W] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q[W], x[I] * inv_d, x[I + 1] * inv_d, 1.0f, B)
+        FGMP_ENC(0, 0, 0); FGMP_ENC(0, 1, 2); FGMP_ENC(0, 2, 4); FGMP_ENC(0, 3, 6);
+        FGMP_ENC(1, 0, 8); FGMP_ENC(1, 1, 10); FGMP_ENC(1, 2, 12); FGMP_ENC(1, 3, 14);
+#undef FGMP_ENC
+#define FGMP_ERR(W, B, I)                                                                \
+    {                                                                                    \
+        const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);      \
+        const float e0 = x[I] - v[0] * d, e1 = x[I + 1] - v[1] * d;                      \
+        t[I] = (e0 * e0) * f[I];                                                         \
+        t[I + 1] = (e1 * e1) * f[I + 1];                                                 \
+    }
+        FGMP_ERR(0, 0, 0) FGMP_ERR(0, 1, 2) FGMP_ERR(0, 2, 4) FGMP_ERR(0, 3, 6)
+        FGMP_ERR(1, 0, 8) FGMP_ERR(1, 1, 10) FGMP_ERR(1, 2, 12) FGMP_ERR(1, 3, 14)
+#undef FGMP_ERR
+#pragma unroll
+        for (int w = 16; w > 1; w >>= 1)
+#pragma unroll
+            for (int i = 0; i < w / 2; ++i) t[i] = t[2 * i] + t[2 * i + 1];
+        const float score = t[0];
+        // (lanes outside the tensor hold zeros: score 0; a negative or -inf threshold must not select them)
+        const uint32_t row = (uint32_t)(rt * kTileRows + rloc);
+        const bool valid = kvalid && row < (uint32_t)p.rows;
+        const bool hi = valid && (score > p.T);
+        const uint64_t ballot = __ballot(hi);
+        const uint32_t tile = (uint32_t)rt * (uint32_t)p.n_kt + kt;
+        if (p.scores != nullptr && valid) p.scores[(int64_t)row * p.nb + kb] = score;
+
+        if constexpr (kMode == kModeF16) {
+            half2_t o[8];
+            if (hi) {
+                float r[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                uint32_t c[4];
+                if (amax * inv_S > 448.0f) encode_fp8_block<true, true>(r, c);
+                else encode_fp8_block<true, false>(r, c);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    o[2 * j] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(c[j], 1.0f, false);
+                    o[2 * j + 1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(c[j], 1.0f, true);
+                }
+            } else {
+                const half2_t s = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sc | (sc << 8), 1.0f, false);
+                o[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 0) * s;
+                o[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 1) * s;
+                o[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 2) * s;
+                o[3] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[0], 1.0f, 3) * s;
+                o[4] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 0) * s;
+                o[5] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 1) * s;
+                o[6] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 2) * s;
+                o[7] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(q[1], 1.0f, 3) * s;
+            }
+            union { half2_t h[8]; uint4 v[2]; } pack;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) pack.h[j] = o[j];
+            // every slot of the tile is written (zeros where the tensor ends), so the GEMM can read whole tiles
+            if (kt < (uint32_t)p.n_kt) {
+                uint4 *dst = reinterpret_cast<uint4 *>(p.x16 + (int64_t)row * p.ld16 + (int64_t)kb * kBlock);
+                dst[0] = pack.v[0];
+                dst[1] = pack.v[1];
+            }
+        } else {
+            const uint32_t prefix = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+            const uint32_t slot = tile * kTileSlots + lane;
+            if (lane == 0) m_lds[it % kQBatch][wave] = make_uint4((uint32_t)ballot, (uint32_t)(ballot >> 32), h_cnt, 0u);
+            uint32_t lw0 = q[0], lw1 = q[1], sbyte = sc;
+            if (ballot != 0ull) {
+                // values beyond the FP8 range only occur when the caller's S is below amax / 448
+                const bool any_big = __ballot(hi && amax * inv_S > 448.0f) != 0ull;
+                if (hi) {
+                    float r[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                    uint32_t c[4];
+                    if (any_big) encode_fp8_block<true, true>(r, c);
+                    else encode_fp8_block<true, false>(r, c);
+                    lw0 = c[0];
+                    lw1 = c[1];
+                    sbyte = prefix;
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{c[2], c[3]}, obuf, (int)(off_H + (h_cnt + prefix) * 8u), 0, 0);
+                }
+            }
+            if (kt < (uint32_t)p.n_kt) {
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{lw0, lw1}, obuf, (int)(off_L + slot * 8u), 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sbyte, obuf, (int)(off_S + slot), 0, 0);
+            }
+            h_cnt += (uint32_t)__popcll(ballot);
+        }
+    };
+    // the gathered plane-M and plane-T words of the last `n` iterations (a batch): 64 and 32 contiguous bytes per row-tile
+    auto write_masks = [&](int it_first, int n) {
+        if constexpr (kMode == kModeStrided) {
+            __syncthreads();
+            const int i = tid / kQWaves, w = tid % kQWaves;
+            const uint32_t kt_w = (uint32_t)(kg * kQWaves + w);
+            if (i < n && kt_w < (uint32_t)p.n_kt) {
+                const uint4 m = m_lds[(it_first + i) % kQBatch][w];
+                const uint32_t tile = (uint32_t)(rt_first + (it_first + i) * rt_step) * (uint32_t)p.n_kt + kt_w;
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{m.x, m.y}, obuf, (int)(off_M + tile * 8u), 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(m.z, obuf, (int)(off_T + tile * 4u), 0, 0);
+            }
+            __syncthreads();
+        }
+    };
+
+    // two row-tiles per turn, each one's input in flight while the other is processed (two register sets
+    // that swap roles: no copies)
+    RawBlock<Tin> a, b;
+    load_block(a);
+    int it = 0;
+    for (; it + 2 <= n_it; it += 2) {
+        load_block(b);
+        process(it, a);
+        load_block(a);
+        process(it + 1, b);
+        if ((it + 2) % kQBatch == 0) write_masks(it + 2 - kQBatch, kQBatch);
+    }
+    if (it < n_it) {
+        process(it, a);
+        ++it;
+    }
+    if (it % kQBatch != 0) write_masks(it - it % kQBatch, it % kQBatch);
+}
+
 // Sensitivity-weighted clipping (Sec. 3.3, Eq. 11): for every block, the E4M3 scale code (0 .. 0x7E)
 // whose NVFP4 quantization has the smallest weighted error -- brute force, candidates in ascending
 // order, a later candidate wins only with a strictly smaller error.  One block per lane; the error of
@@ -456,7 +693,32 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
             else hipLaunchKernelGGL((clip_scales_kernel<uint16_t, false, kUseHwCvt>), cgrid, dim3(256), 0, st, p, clip_scales);
         }
     }
-    if (x16 != nullptr) {
+    // The activation hot path (one pass, NVFP4-error score, one sensitivity per channel, dynamic-max
+    // scales) runs on the trimmed kernel when its 32-bit offsets and its shortcut division apply.
+    const uint64_t x_bytes = (uint64_t)rows * (uint64_t)ldx * (uint64_t)esz;
+    // (offsets: the input plus one stride of the resident set past its end must stay below 2^32)
+    const bool fast = kUseHwCvt && !compact && !per_elem && !p.delta && clip_scales == nullptr &&
+                      x_bytes < 0x7FFFFF00ull && l.total_bytes < 0xFFFFFF00ull && S >= 1e-30f && S <= 1e30f &&
+                      l.n_tiles >= kQMinTiles;
+    if (fast) {
+        p.mode = x16 != nullptr ? kModeF16 : kModeStrided;
+        // one resident set of workgroups (three of eight waves per compute unit), a multiple of the number of
+        // K groups, with the row-tiles dealt out evenly
+        const int64_t n_kg = (l.n_kt + kQWaves - 1) / kQWaves;
+        int64_t gy = std::max<int64_t>(1, (int64_t)768 / n_kg);
+        if (gy > l.n_rt) gy = l.n_rt;
+        const int64_t its = (l.n_rt + gy - 1) / gy;
+        gy = (l.n_rt + its - 1) / its;
+        const dim3 fgrid((unsigned)(n_kg * gy));
+        const uint32_t out_bytes = packed ? (uint32_t)(x16 != nullptr ? sizeof(PackedHeader) : l.total_bytes) : 0u;
+        if (x16 != nullptr) {
+            if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeF16>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+            else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeF16>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+        } else {
+            if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeStrided>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+            else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeStrided>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+        }
+    } else if (x16 != nullptr) {
         p.mode = kModeF16;
         if (dt == FGMP_F32) launch_quantize<float>(p, per_elem, grid, st);
         else launch_quantize<uint16_t>(p, per_elem, grid, st);
