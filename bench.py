@@ -131,7 +131,7 @@ def main() -> int:
     w_info = fgmp.packed_info(pW)
 
     Y = torch.empty((M, N), dtype=torch.float32, device=dev)
-    ws = torch.empty(fgmp.workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
+    ws = fgmp.new_workspace(fgmp.workspace_bytes(M, N, K), dev)
     pX = fgmp.quantize_activations(xd, fxd, Tx, sx)
     x_info = fgmp.packed_info(pX)
 
@@ -301,7 +301,7 @@ def main() -> int:
             for Md in (1, 8, 32):
                 pXd = fgmp.quantize_activations(xk[:Md].contiguous(), fxk, 1e-3, sx)
                 Yd = torch.empty((Md, Nd), dtype=torch.float32, device=dev)
-                wsd = torch.empty(fgmp.workspace_bytes(Md, Nd, Kd), dtype=torch.uint8, device=dev)
+                wsd = fgmp.new_workspace(fgmp.workspace_bytes(Md, Nd, Kd), dev)
                 xmd = xk[:Md].contiguous()
                 it = [0]
 
@@ -353,7 +353,7 @@ def main() -> int:
         Txp = fgmp.threshold_for_fraction(sc_x, p_x)
         del sc_x
         Yp = torch.empty((Mp_, Np_), dtype=torch.float32, device=dev)
-        wsp = torch.empty(fgmp.workspace_bytes(Mp_, Np_, Kp_), dtype=torch.uint8, device=dev)
+        wsp = fgmp.new_workspace(fgmp.workspace_bytes(Mp_, Np_, Kp_), dev)
         ms_p = timed(lambda: fgmp.quant_gemm_fused(xp, fxp, Txp, sxp, pWp, out=Yp, workspace=wsp), 50, 10)
         info = fgmp.packed_info(pWp)
         return {"ms_per_step": round(ms_p, 4), "TFLOPs": round(2.0 * Mp_ * Np_ * Kp_ / (ms_p * 1e-3) / 1e12, 1),
@@ -386,7 +386,7 @@ def main() -> int:
         del Ws
         Fxs = [torch.from_numpy(synth.fisher_per_channel(Kl, 0, 310 + li)).to(dev) for li, (_, Kl, _) in enumerate(shapes)]
         Ys = [torch.empty((M, Nl), dtype=torch.float32, device=dev) for _, _, Nl in shapes]
-        wss = [torch.empty(fgmp.workspace_bytes(M, Nl, Kl), dtype=torch.uint8, device=dev) for _, Kl, Nl in shapes]
+        wss = [fgmp.new_workspace(fgmp.workspace_bytes(M, Nl, Kl), dev) for _, Kl, Nl in shapes]
 
         def layer_input(li):
             return xd if li == 0 else Ys[li - 1][:, :shapes[li][1]]
@@ -429,7 +429,7 @@ def main() -> int:
         T_y = fgmp.threshold_for_fraction(scy, P_FP8)
         del scy
         pY = fgmp.quantize_activations(Y, f_n, T_y, s_y)
-        ws_po = torch.empty(int(fgmp.lib().fgmp_workspace_bytes_packed_out(M, N, K)), dtype=torch.uint8, device=dev)
+        ws_po = fgmp.new_workspace(fgmp.lib().fgmp_workspace_bytes_packed_out(M, N, K), dev)
         ms_po = timed(lambda: fgmp.quant_gemm_fused_packed_out(xd, fxd, Tx, sx, pW, f_n, T_y, s_y, out=pY,
                                                                workspace=ws_po), 100, 20)
 
@@ -472,8 +472,8 @@ def main() -> int:
         del scx
         # calibration of the intermediate tensor (scale, threshold) from one unfused pass
         Y1 = torch.empty((Mm, Nf), dtype=torch.float32, device=dev)
-        ws1 = torch.empty(fgmp.workspace_bytes(Mm, Nf, Kh), dtype=torch.uint8, device=dev)
-        ws2 = torch.empty(fgmp.workspace_bytes(Mm, Kh, Nh), dtype=torch.uint8, device=dev)
+        ws1 = fgmp.new_workspace(fgmp.workspace_bytes(Mm, Nf, Kh), dev)
+        ws2 = fgmp.new_workspace(fgmp.workspace_bytes(Mm, Kh, Nh), dev)
         Z = torch.empty((Mm, Kh), dtype=torch.float32, device=dev)
 
         def framework_gate():
@@ -486,8 +486,7 @@ def main() -> int:
         T_h = fgmp.threshold_for_fraction(sch, P_FP8)
         del sch
         pH = fgmp.quantize_activations(hb, fh, T_h, s_h)
-        ws_g = torch.empty(int(fgmp.lib().fgmp_workspace_bytes_packed_out_ex(Mm, Nf, Kh, fgmp.EPILOGUE_SILU_GATE)),
-                           dtype=torch.uint8, device=dev)
+        ws_g = fgmp.new_workspace(fgmp.lib().fgmp_workspace_bytes_packed_out_ex(Mm, Nf, Kh, fgmp.EPILOGUE_SILU_GATE), dev)
 
         def fc1_gated():
             fgmp.quant_gemm_fused_packed_out(xg, fx1, Txg, sxg, pW1, fh, T_h, s_h, out=pH, workspace=ws_g,
@@ -524,7 +523,7 @@ def main() -> int:
         for Ms in (64, 128, 256):
             xs_ = xd[:Ms].contiguous()
             Ys = torch.empty((Ms, N), dtype=torch.float32, device=dev)
-            wss = torch.empty(fgmp.workspace_bytes(Ms, N, K), dtype=torch.uint8, device=dev)
+            wss = fgmp.new_workspace(fgmp.workspace_bytes(Ms, N, K), dev)
             it = [0]
 
             def call_small():

@@ -21,6 +21,11 @@
  *     the outputs are unspecified; argument errors are detected on the host
  *     before anything is launched.
  *   - Inputs must be finite; NaN/Inf inputs give unspecified codes.
+ *   - A workspace starts with FGMP_WORKSPACE_CONTROL_BYTES of arrival counters.  They must be zero
+ *     when the workspace is first used (clear that much once after allocating it; nothing else in a
+ *     workspace needs initializing) and every call leaves them zero, so a workspace can be reused
+ *     for any sequence of calls and shapes, in or outside a captured graph.  Calls that may overlap
+ *     in time need workspaces of their own.
  *   - A packed tensor is an opaque, self-describing device buffer.  Writing one
  *     needs fgmp_packed_bytes(rows, K) bytes (worst case: every block FP8); once
  *     written, its first `bytes_used` bytes (fgmp_packed_info) are all that any
@@ -35,6 +40,8 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+#define FGMP_WORKSPACE_CONTROL_BYTES 65536
 
 typedef int fgmp_status_t;
 enum {
@@ -160,7 +167,8 @@ fgmp_status_t fgmp_quant_gemm_fused(const void *X, fgmp_dtype_t dt, int64_t M, i
  * FGMP_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.  The
  * call allocates nothing and frees nothing; same arguments, results (bit for bit) and errors as
  * fgmp_quant_gemm_fused, without the workspace.
- *   limit      fgmp_workspace_bytes(M, N, K) <= FGMP_STATIC_SCRATCH_BYTES, else
+ *   limit      the scratch this call uses (never more than fgmp_workspace_bytes(M, N, K); less for the
+ *              decode shapes that one kernel handles) <= FGMP_STATIC_SCRATCH_BYTES, else
  *              FGMP_ERR_BUFFER_TOO_SMALL and nothing is launched (all decode shapes, M <= 32, of the
  *              Llama-2-7B linears fit; prefill shapes generally do not)
  *   sharing    every call on a GPU uses that GPU's one array: calls that overlap in time on the

@@ -87,7 +87,7 @@ fgmp_status_t fgmp_quant_gemm_fused_static_scratch(const void *X, fgmp_dtype_t d
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (K % kBlock != 0) return FGMP_ERR_BAD_SHAPE;
     // the size check comes first: a product that does not fit must not touch the array
-    if (gemm_workspace_bytes(M, N, K) > (size_t)FGMP_STATIC_SCRATCH_BYTES) return FGMP_ERR_BUFFER_TOO_SMALL;
+    if (quant_gemm_workspace_need(M, N, K) > (size_t)FGMP_STATIC_SCRATCH_BYTES) return FGMP_ERR_BUFFER_TOO_SMALL;
     void *ws = nullptr;
     const fgmp_status_t rc = static_scratch(&ws);
     if (rc != FGMP_OK) return rc;

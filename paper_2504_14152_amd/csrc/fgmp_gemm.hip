@@ -256,30 +256,43 @@ static size_t skinny_x16_bytes(int64_t M, int64_t K)
     return (size_t)align_up((uint64_t)gemm_skinny_x16_rows(M) * round_up(K, kTileK) * 2, 256);
 }
 
+// (all of these count the bytes behind the control region)
 size_t gemm_only_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    return gemm_skinny_applies(M, N, K) ? skinny_x16_bytes(M, K) + gemm_skinny_workspace_bytes(M, N, K)
-                                        : gemm_ws_layout(M, N, K).total;
+    const size_t other = gemm_skinny_applies(M, N, K) ? skinny_x16_bytes(M, K) + gemm_skinny_workspace_bytes(M, N, K)
+                                                      : gemm_ws_layout(M, N, K).total;
+    return std::max(other, gemm_stream_scratch_bytes(M, N, K));
 }
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     // the fused call also keeps the quantized activations here: packed, or header + FP16 values
-    return (size_t)make_layout(M, K).total_bytes + gemm_only_workspace_bytes(M, N, K);
+    return kWsCtrlRegion + (size_t)make_layout(M, K).total_bytes + gemm_only_workspace_bytes(M, N, K);
 }
 
+size_t quant_gemm_workspace_need(int64_t M, int64_t N, int64_t K)
+{
+    if (gemm_stream_applies(M, N, K)) return kWsCtrlRegion + gemm_stream_scratch_bytes(M, N, K);
+    return gemm_workspace_bytes(M, N, K);
+}
+
+// `skip`: bytes behind the control region that the caller keeps for itself (the fused call's packed activations)
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
-                          float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st)
+                          float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st, size_t skip)
 {
     if (!packed_X || !packed_W || !Y || !workspace) return FGMP_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (K % kBlock != 0 || ldy < N) return FGMP_ERR_BAD_SHAPE;
     if (((uintptr_t)packed_X | (uintptr_t)packed_W | (uintptr_t)Y | (uintptr_t)workspace) % 16 != 0)
         return FGMP_ERR_BAD_ALIGN;
-    if (workspace_bytes < gemm_only_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
+    if (workspace_bytes < kWsCtrlRegion + skip + gemm_only_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
     const PackedLayout la = make_layout(M, K), lb = make_layout(N, K);
     const PackedView A = make_view(const_cast<void *>(packed_X), la);
     const PackedView B = make_view(const_cast<void *>(packed_W), lb);
+    void *const ctrl = workspace;
+    workspace = static_cast<char *>(workspace) + kWsCtrlRegion + skip;
+    if (gemm_stream_applies(M, N, K))
+        return gemm_stream(2, nullptr, 0, nullptr, 0.0f, 1.0f, packed_X, M, packed_W, N, K, Y, ldy, ctrl, workspace, st);
     if (gemm_skinny_applies(M, N, K)) {
         // decode shapes: expand the few activation rows to FP16 once, then stream the weights
         _Float16 *x16 = static_cast<_Float16 *>(workspace);
@@ -331,8 +344,23 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
     if (K % kBlock != 0 || ldy < N) return FGMP_ERR_BAD_SHAPE;
     if (((uintptr_t)workspace | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
-    if (workspace_bytes < gemm_workspace_bytes(M, N, K)) return FGMP_ERR_BUFFER_TOO_SMALL;
-    char *ws = static_cast<char *>(workspace);
+    // (the one-launch kernel addresses X with 32-bit byte offsets)
+    const bool x_fits = ldx > 0 && ldx < (int64_t)0xFFFFFF00 / (M * 4);
+    const bool stream = score_mode == FGMP_SCORE_NVFP4_ERROR && pack_out == nullptr && x_fits && gemm_stream_applies(M, N, K);
+    if (workspace_bytes < (stream ? quant_gemm_workspace_need(M, N, K) : gemm_workspace_bytes(M, N, K)))
+        return FGMP_ERR_BUFFER_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace) + kWsCtrlRegion;
+    if (stream) {
+        // decode shapes: one launch quantizes the activation rows and streams the weights
+        if (!X || !fisher_k || !Y) return FGMP_ERR_INVALID_ARG;
+        if (dt != FGMP_F32 && dt != FGMP_BF16) return FGMP_ERR_UNSUPPORTED;
+        if (!(scale_x > 0.0f) || !(scale_x < INFINITY) || threshold != threshold) return FGMP_ERR_INVALID_ARG;
+        const int64_t esz = dt == FGMP_F32 ? 4 : 2;
+        if (ldx < K) return FGMP_ERR_BAD_SHAPE;
+        if (((uintptr_t)X | (uintptr_t)fisher_k) % 16 != 0 || (ldx * esz) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
+        return gemm_stream(dt == FGMP_F32 ? 1 : 0, X, ldx, fisher_k, threshold, scale_x, nullptr, M, packed_W, N, K, Y, ldy,
+                           workspace, ws, st);
+    }
     const bool in_kernel_prefill = !gemm_skinny_applies(M, N, K) && mixed_kernel_applies(N, K) && kUseHwCvt;
     if (pack_out != nullptr && !in_kernel_prefill) return FGMP_ERR_UNSUPPORTED;   // the caller falls back
     if (gemm_skinny_applies(M, N, K) && kUseHwCvt) {
@@ -370,7 +398,8 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
     const fgmp_status_t rc = quantize_tensor(X, dt, M, K, ldx, fisher_k, 0, threshold, scale_x, ws, xbytes,
                                              nullptr, false, st, nullptr, 0, nullptr, 0, score_mode);
     if (rc != FGMP_OK) return rc;
-    return gemm_packed(ws, M, packed_W, N, K, Y, ldy, ws + xbytes, workspace_bytes - xbytes, st);
+    // (the packed activations sit behind the control region; the product's own workspace starts with one)
+    return gemm_packed(ws, M, packed_W, N, K, Y, ldy, workspace, workspace_bytes, st, xbytes);
 }
 
 // Fused call whose results are quantized and packed instead of stored as FP32 (Sec. 4.2).  Prefill

@@ -27,8 +27,11 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
 fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
                             uint8_t *mask, hipStream_t st);
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,
-                          float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st);
+                          float *Y, int64_t ldy, void *workspace, size_t workspace_bytes, hipStream_t st,
+                          size_t skip = 0);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// what fgmp_quant_gemm_fused itself uses of a workspace (control region included)
+size_t quant_gemm_workspace_need(int64_t M, int64_t N, int64_t K);
 struct PackOut;
 // quantize X and multiply in one call; `workspace` holds at least gemm_workspace_bytes(M, N, K)
 fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx, const float *fisher_k,
@@ -57,6 +60,17 @@ SkinnyCounters gemm_skinny_counters(int64_t M, int64_t N, int64_t K, void *works
 fgmp_status_t gemm_skinny(const PackedHeader *xh, const PackedLayout &lx, const _Float16 *x16, int64_t ld16,
                           const void *w, const PackedLayout &lw, int64_t M, int64_t N, int64_t K, float *Y,
                           int64_t ldy, void *workspace, hipStream_t st);
+// Every workspace starts with a control region: arrival counters that must be zero when a call starts and
+// that every call leaves zero (the caller clears them once, after allocating).  Nothing but the
+// single-launch decode kernel touches it; all other scratch starts behind it.
+constexpr size_t kWsCtrlRegion = FGMP_WORKSPACE_CONTROL_BYTES;
+// Decode shapes (M <= 32) in one launch: the activations are quantized (src 0: bf16 X, 1: fp32 X) or
+// decoded (src 2: packed X) inside the kernel that streams the weights.
+bool gemm_stream_applies(int64_t M, int64_t N, int64_t K);
+size_t gemm_stream_scratch_bytes(int64_t M, int64_t N, int64_t K);
+fgmp_status_t gemm_stream(int src, const void *X, int64_t ldx, const float *fisher, float T, float S, const void *packed_X,
+                          int64_t M, const void *packed_W, int64_t N, int64_t K, float *Y, int64_t ldy, void *ctrl,
+                          void *scratch, hipStream_t st);
 // packed -> zero-padded dense FP16 [8 n_rt_pad][ld]; one launch decodes one or two tensors and
 // can clear `zero_n` 32-bit counters
 struct DecodeJob {

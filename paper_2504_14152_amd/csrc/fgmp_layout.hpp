@@ -13,7 +13,8 @@
 //             first 8 E4M3 bytes of an FP8 block.
 //   plane S   1 byte per slot (64 B per tile): the E4M3 block scale of an FP4
 //             block; for an FP8 block, which has no scale, the index of its
-//             entry among the tile's entries in plane H.
+//             entry among the tile's entries in plane H -- the number of FP8
+//             slots before it in the tile (readers may take it from the mask).
 //   plane M   one 64-bit word per tile: bit j set = slot j is FP8.
 //   plane T   one uint32 per tile: index (in 8-byte entries) of the tile's
 //             first entry in plane H.
@@ -23,8 +24,9 @@
 //             choice (T[t] = 64 t, or the tiles one wave visits appended one
 //             after the other) and readers only go by T[t].  "compact" tensors
 //             (weights, packed offline) store the entries back to back in tile
-//             order, so the tensor occupies 9 B per FP4 block and 16 B per FP8
-//             block plus tables.
+//             order -- T[t + 1] = T[t] + number of FP8 slots of tile t -- so
+//             the tensor occupies 9 B per FP4 block and 16 B per FP8 block
+//             plus tables.
 //   Slots outside the tensor (row >= rows or K-block >= K/16) hold FP4 zeros.
 //
 // A 256-byte header precedes the planes; every plane starts 256-byte aligned.

@@ -190,6 +190,17 @@ def workspace_bytes(M: int, N: int, K: int) -> int:
     return int(lib().fgmp_workspace_bytes(M, N, K))
 
 
+WORKSPACE_CONTROL_BYTES = 65536   # FGMP_WORKSPACE_CONTROL_BYTES
+
+
+def new_workspace(nbytes: int, device) -> torch.Tensor:
+    """A workspace of `nbytes` whose control region (the arrival counters at its start) is zero, as
+    the library requires of a workspace's first use; the rest is left uninitialized."""
+    ws = torch.empty(int(nbytes), dtype=torch.uint8, device=device)
+    ws[:min(int(nbytes), WORKSPACE_CONTROL_BYTES)].zero_()
+    return ws
+
+
 def _alloc_packed(rows: int, K: int, device) -> Packed:
     n = packed_bytes(rows, K)
     if n == 0:
@@ -260,7 +271,7 @@ def gemm(pX: Packed, pW: Packed, out: torch.Tensor | None = None, workspace: tor
     M, N, K = pX.rows, pW.rows, pX.K
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=pX.buf.device)
     if workspace is None:
-        workspace = torch.empty(workspace_bytes(M, N, K), dtype=torch.uint8, device=pX.buf.device)
+        workspace = new_workspace(workspace_bytes(M, N, K), pX.buf.device)
     ws_n = workspace.numel()
     rc = lib().fgmp_gemm(_ptr(pX.buf), M, _ptr(pW.buf), N, K, _ptr(Y), Y.stride(0), _ptr(workspace), ws_n,
                          _stream())
@@ -278,7 +289,7 @@ def quant_gemm_fused(X: torch.Tensor, fisher_k: torch.Tensor, threshold: float, 
     N = pW.rows
     Y = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=X.device)
     if workspace is None:
-        workspace = torch.empty(workspace_bytes(M, N, K), dtype=torch.uint8, device=X.device)
+        workspace = new_workspace(workspace_bytes(M, N, K), X.device)
     if score_mode is None:
         rc = lib().fgmp_quant_gemm_fused(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
                                          float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(Y), Y.stride(0),
@@ -325,7 +336,7 @@ def quant_gemm_fused_packed_out(X: torch.Tensor, fisher_k: torch.Tensor, thresho
     scores = torch.empty((M, n_out // 16), dtype=torch.float32, device=X.device) if want_scores else None
     if epilogue is None:
         if workspace is None:
-            workspace = torch.empty(int(lib().fgmp_workspace_bytes_packed_out(M, N, K)), dtype=torch.uint8, device=X.device)
+            workspace = new_workspace(lib().fgmp_workspace_bytes_packed_out(M, N, K), X.device)
         rc = lib().fgmp_quant_gemm_fused_packed_out(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
                                                     float(threshold), float(scale_x), _ptr(pW.buf), N, _ptr(fisher_n),
                                                     float(threshold_y), float(scale_y), _ptr(out.buf), out.buf.numel(),
@@ -333,8 +344,7 @@ def quant_gemm_fused_packed_out(X: torch.Tensor, fisher_k: torch.Tensor, thresho
         _check(rc, "fgmp_quant_gemm_fused_packed_out")
     else:
         if workspace is None:
-            workspace = torch.empty(int(lib().fgmp_workspace_bytes_packed_out_ex(M, N, K, int(epilogue))),
-                                    dtype=torch.uint8, device=X.device)
+            workspace = new_workspace(lib().fgmp_workspace_bytes_packed_out_ex(M, N, K, int(epilogue)), X.device)
         rc = lib().fgmp_quant_gemm_fused_packed_out_ex(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k),
                                                        float(threshold), float(scale_x), _ptr(pW.buf), N, int(epilogue),
                                                        _ptr(fisher_n), float(threshold_y), float(scale_y), _ptr(out.buf),

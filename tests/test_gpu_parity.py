@@ -970,15 +970,65 @@ def test_hand_counted_waits_against_full_waits(M, K, N):
     assert torch.isfinite(Y).all() and torch.equal(Y, Y_full)
 
 
-@pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (300, 512, 520), (70, 1024, 512)])
+@pytest.mark.parametrize("M,K,N,dtype", [(1, 4096, 12288, "bf16"), (8, 4096, 22016, "bf16"), (8, 11008, 4096, "fp32"),
+                                          (32, 4096, 4096, "bf16"), (13, 1152, 528, "fp32"), (3, 28672, 8192, "bf16")])
+def test_decode_kernel_hand_counted_waits_against_full_waits(M, K, N, dtype):
+    """The same guard for the one-launch decode kernel, whose loads are assembly with counted waits as
+    well: the build in which every wait is a full one must give the same Y bit for bit.  Runs of eight
+    tiles per wave (first pass of the ring plus one turn), long runs that cross row groups, K in three,
+    four and four parts across workgroups (counters, partial sums), both row-group widths, both input
+    types, a ragged K."""
+    from paper_2504_14152_amd import build
+    _say(f"decode kernel, counted waits vs full waits {M}x{K}x{N} {dtype}")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(190 + N)
+    wd = torch.empty((N, K), dtype=torch.bfloat16, device=DEV).normal_(0.0, 0.02, generator=gen)
+    x = synth.activations(M, K, 91, 1)
+    xd, xref = (torch.from_numpy(x).to(DEV), x) if dtype == "fp32" else _to_dev_bf16(x)
+    fxd = torch.from_numpy(synth.fisher_per_channel(K, 91, 3)).to(DEV)
+    sx, sw = float(synth.default_tensor_scale(xref)), float(wd.abs().max().float()) / 448.0
+    _, sws = fgmp.quantize_weights(wd, fxd, np.inf, sw, want_scores=True)
+    pW = fgmp.quantize_weights(wd, fxd, fgmp.threshold_for_fraction(sws, 0.2), sw)
+    del sws, wd
+    Tx = fgmp.threshold_for_fraction(fgmp.quantize_activations(xd, fxd, np.inf, sx, want_scores=True)[1], 0.2)
+    ws = fgmp.new_workspace(fgmp.workspace_bytes(M, N, K), DEV)
+    Y = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW, workspace=ws)
+    assert not bool(ws[:fgmp.WORKSPACE_CONTROL_BYTES].any()), "every call leaves the control region zero"
+    pX = fgmp.quantize_activations(xd, fxd, Tx, sx)
+    Yp = fgmp.gemm(pX, pW)
+    assert torch.equal(Y, Yp), "quantizing in the kernel and decoding packed activations give the same operand values"
+    with fgmp.use_library(build.lib_path("fullwait")):
+        Y_full = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW)
+    assert torch.isfinite(Y).all() and torch.equal(Y, Y_full)
+
+
+def test_decode_kernel_reads_weights_that_are_not_compact():
+    """A tensor packed the way activations are (room for 64 plane-H entries per tile, wherever the writer
+    put them) is a valid W: the decode kernel then takes every tile's first entry from plane T instead of
+    counting on from the tile before.  Same codes as the compact tensor, same order of summation: the
+    same Y bit for bit."""
+    M, K, N = 8, 2048, 1056
+    c = _quantized_pair(M, K, N, 77, 0.3, per_elem_w=False)
+    wd, _ = _to_dev_bf16(c["wref"])
+    fwd = torch.from_numpy(c["fw"]).to(DEV)
+    pW_strided = fgmp.quantize_activations(wd, fwd, c["Tw"], c["sw"])
+    assert fgmp.packed_info(pW_strided)["compact"] == 0 and fgmp.packed_info(c["pW"])["compact"] == 1
+    Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    _check_gemm(c, Y, label="decode kernel, compact W")
+    Ys = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], pW_strided)
+    assert torch.equal(Y, Ys)
+
+
+@pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (8, 11008, 512), (24, 2048, 520), (300, 512, 520), (70, 1024, 512)])
 def test_fused_call_replays_in_a_hip_graph(M, K, N):
     """The hot-path calls only enqueue kernels on the caller's stream (no allocation, no synchronization,
-    no memset nodes: arrival counters are cleared by the kernel that prepares the activations), so a
-    captured step can be replayed: a decode shape (split-K counters), a prefill shape whose tiles are
-    computed in two parts, and a decode shape of three row chunks.  Every replay, with eager work and synchronizations in between, must
+    no memset nodes: arrival counters are put back to zero by the kernels that use them), so a
+    captured step can be replayed: decode shapes (one launch; with K in one part and in three parts that
+    meet at the row groups' counters; the older two-kernel path for an odd number of row-tiles), a prefill
+    shape whose tiles are computed in two parts, and a decode shape of three row chunks.  Every replay, with eager work and synchronizations in between, must
     reproduce the eager result bit for bit."""
     c = _quantized_pair(M, K, N, 43, 0.1, per_elem_w=False)
-    ws = torch.empty(fgmp.workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
+    ws = fgmp.new_workspace(fgmp.workspace_bytes(M, N, K), DEV)
     Y_eager = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], workspace=ws).clone()
     Y = torch.empty_like(Y_eager)
     side = torch.cuda.Stream()
@@ -992,7 +1042,8 @@ def test_fused_call_replays_in_a_hip_graph(M, K, N):
         fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], out=Y, workspace=ws)
     for rep in range(4):
         Y.zero_()
-        ws.fill_(0xA5 if rep & 1 else 0)          # whatever the workspace holds between replays
+        ws[fgmp.WORKSPACE_CONTROL_BYTES:].fill_(0xA5 if rep & 1 else 0)   # whatever the scratch holds between replays
+        assert not bool(ws[:fgmp.WORKSPACE_CONTROL_BYTES].any()), "every call leaves the control region zero"
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
