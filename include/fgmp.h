@@ -307,7 +307,10 @@ fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host
 
 /* Threshold for a target fraction of FP8 blocks (Eq. 9): the score below the
  * round(fraction*J) largest of the J device-resident scores; fraction 0 ->
- * +INF, 1 -> -INF.  threshold_host: host. */
+ * +INF, 1 -> -INF.  threshold_host: host.  Found on the device (an exact radix
+ * selection: four passes over the scores, which stay where they are); the call
+ * allocates a few KB of device memory for its counters, synchronizes `stream`
+ * and frees them. */
 fgmp_status_t fgmp_threshold_for_fraction(const float *scores, int64_t J, double fraction,
                                           float *threshold_host, void *stream);
 
@@ -316,7 +319,8 @@ fgmp_status_t fgmp_threshold_for_fraction(const float *scores, int64_t J, double
  * every layer), so that layers keep different fractions of their blocks in FP8
  * while the total matches `fraction`.
  *   scores  host array of n_tensors device pointers; counts  host array of their lengths
- * Synchronizes `stream`; uses host memory for the union. */
+ * The union is never formed: every pass of the selection counts over all the arrays.  Synchronizes
+ * `stream`. */
 fgmp_status_t fgmp_threshold_for_fraction_multi(const float *const *scores, const int64_t *counts,
                                                 int32_t n_tensors, double fraction, float *threshold_host,
                                                 void *stream);

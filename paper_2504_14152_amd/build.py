@@ -18,7 +18,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfgmp.so")
 SOURCES = ["fgmp_quantize.hip", "fgmp_gemm.hip", "fgmp_gemm_skinny.hip", "fgmp_gemm_stream.hip", "fgmp_gemm_mixed.hip",
-           "fgmp_api.hip"]
+           "fgmp_select.hip", "fgmp_api.hip"]
 # -ffp-contract=off: the quantizer's FP32 steps are separately rounded.
 # packed-fp32-ops is switched off for the device compiler on purpose.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -236,19 +236,6 @@ fgmp_status_t fgmp_packed_info(const void *packed, fgmp_packed_info_t *info_host
     return FGMP_OK;
 }
 
-// Eq. 9 / Eq. 10 read as: exactly round(fraction * J) of the J scores lie strictly above the threshold
-static fgmp_status_t threshold_of_host_scores(std::vector<float> &host, double fraction, float *threshold_host)
-{
-    const int64_t J = (int64_t)host.size();
-    const int64_t n_hi = (int64_t)(fraction * (double)J + 0.5);
-    if (n_hi <= 0) { *threshold_host = INFINITY; return FGMP_OK; }
-    if (n_hi >= J) { *threshold_host = -INFINITY; return FGMP_OK; }
-    auto nth = host.begin() + (J - n_hi - 1);
-    std::nth_element(host.begin(), nth, host.end());
-    *threshold_host = *nth;
-    return FGMP_OK;
-}
-
 fgmp_status_t fgmp_threshold_for_fraction(const float *scores, int64_t J, double fraction,
                                           float *threshold_host, void *stream)
 {
@@ -266,17 +253,12 @@ fgmp_status_t fgmp_threshold_for_fraction_multi(const float *const *scores, cons
         if (!scores[i] || counts[i] <= 0) return FGMP_ERR_INVALID_ARG;
         total += counts[i];
     }
-    hipStream_t st = as_stream(stream);
-    std::vector<float> host((size_t)total);
-    size_t at = 0;
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        if (hipMemcpyAsync(host.data() + at, scores[i], (size_t)counts[i] * sizeof(float), hipMemcpyDeviceToHost,
-                           st) != hipSuccess)
-            return FGMP_ERR_HIP;
-        at += (size_t)counts[i];
-    }
-    if (hipStreamSynchronize(st) != hipSuccess) return FGMP_ERR_HIP;
-    return threshold_of_host_scores(host, fraction, threshold_host);
+    // Eq. 9 / Eq. 10 read as: exactly round(fraction * J) of the J scores lie strictly above the threshold
+    // (when the boundary score is not tied): the score just below the round(fraction * J) largest ones
+    const int64_t n_hi = (int64_t)(fraction * (double)total + 0.5);
+    if (n_hi <= 0) { *threshold_host = INFINITY; return FGMP_OK; }
+    if (n_hi >= total) { *threshold_host = -INFINITY; return FGMP_OK; }
+    return select_rank(scores, counts, n_tensors, total - n_hi - 1, threshold_host, as_stream(stream));
 }
 
 fgmp_status_t fgmp_selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *max_bits,

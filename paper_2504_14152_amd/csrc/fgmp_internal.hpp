@@ -114,6 +114,9 @@ fgmp_status_t selftest_encode_ranges(int format, uint32_t *min_bits, uint32_t *m
                                      uint32_t *violations, hipStream_t st);
 fgmp_status_t selftest_decode_table(int format, float *out, hipStream_t st);
 fgmp_status_t selftest_mfma_rate(int64_t workgroups, int32_t iters, float *sink, hipStream_t st);
+// element of rank `rank` (0 = smallest) of the union of n_tensors device arrays; result on the host; synchronizes
+fgmp_status_t select_rank(const float *const *scores, const int64_t *counts, int32_t n_tensors, int64_t rank, float *result_host,
+                          hipStream_t st);
 // events recorded around every launch of the prefill GEMM kernel (both null: none); false when the
 // library was built without the measurement hooks
 bool set_gemm_kernel_events(hipEvent_t start, hipEvent_t stop);

@@ -393,6 +393,117 @@ def test_global_threshold_over_layers():
     assert fgmp.threshold_for_fraction_multi(dev_scores[:1], p) == fgmp.threshold_for_fraction(dev_scores[0], p)
 
 
+@pytest.mark.parametrize("case", ["ties", "signed", "tiny", "ragged union", "large"])
+def test_threshold_selection_on_the_device_is_the_exact_order_statistic(case):
+    """The threshold helper selects on the device (radix selection over the score arrays where they
+    are); its result is the oracle's order statistic bit for bit: boundary scores tied many times over,
+    negative scores and both zeros (the Eq. 8 score can be negative), arrays of one to five elements,
+    a union of arrays of odd lengths that start at odd addresses, and 20 M scores in three arrays."""
+    rng = synth.rng_for(5, {"ties": 1, "signed": 2, "tiny": 3, "ragged union": 4, "large": 5}[case])
+    if case == "ties":
+        arrays = [rng.integers(0, 7, size=100003).astype(np.float32) * np.float32(0.37)]
+    elif case == "signed":
+        a = rng.standard_normal(65537).astype(np.float32)
+        a[::17] = 0.0
+        a[5::19] = -0.0
+        arrays = [a, -np.abs(rng.standard_normal(1001)).astype(np.float32) * np.float32(1e-30)]
+    elif case == "tiny":
+        arrays = [np.array([3.0], np.float32), np.array([1.0, 1.0], np.float32), np.array([2.0, -5.0], np.float32)]
+    elif case == "ragged union":
+        arrays = [rng.standard_exponential(n).astype(np.float32) for n in (1, 2, 3, 5, 63, 257, 4099, 70001)]
+    else:
+        arrays = [(rng.standard_exponential(n).astype(np.float32) ** 2) for n in (12_000_001, 7_999_999, 5)]
+    # device copies at odd element offsets inside larger buffers (the kernel reads 16 bytes per lane where it can)
+    dev = []
+    for i, a in enumerate(arrays):
+        buf = torch.empty(a.size + 8, dtype=torch.float32, device=DEV)
+        off = 1 + i % 3
+        buf[off:off + a.size] = torch.from_numpy(a).to(DEV)
+        dev.append(buf[off:off + a.size])
+    union = np.concatenate(arrays)
+    for p in ((0.1, 0.5, 1.0 - 1.0 / union.size) if case == "large" else (0.0, 1.0, 0.5, 0.1, 0.9, 1.0 / union.size, 1.0 - 1.0 / union.size, 0.3333)):
+        want = orc.threshold(union, p)
+        got = fgmp.threshold_for_fraction_multi(dev, p)
+        assert got == want or (np.isnan(got) and np.isnan(want)), (case, p, got, want)
+        assert (union > np.float32(got)).sum() <= int(p * union.size + 0.5)
+    assert fgmp.threshold_for_fraction(dev[0], 0.25) == orc.threshold(arrays[0], 0.25)
+
+
+def _exactly_summable(ax, aw):
+    """True if every partial sum of ax @ aw.T, in any order, is an fp32 number: all products are multiples
+    of one power of two, and the largest sum of magnitudes is below 2**24 of them."""
+    def unit(a):
+        m, e = np.frexp(np.abs(a[a != 0]).astype(np.float64))
+        mi = (m * 2.0 ** 53).astype(np.int64)
+        low = mi & -mi                                   # lowest set bit of the 53-bit significand
+        return (e - 53 + np.log2(low.astype(np.float64)).astype(np.int64)).min()
+    return float((np.abs(ax) @ np.abs(aw).T).max()) / 2.0 ** float(unit(ax) + unit(aw)) < 2.0 ** 24
+
+
+def test_layer_chain_with_global_thresholds_matches_oracle_stage_by_stage():
+    """Three linears in a row as a decoder layer runs them (Sec. 5.3): QKV-like product -> its FP32 result
+    is the next input -> FC1 with the gated activation and output-side quantization (packed H never
+    leaves as FP32) -> FC2 from the packed tensor.  One threshold for all weights and one for all
+    activations (Eq. 10), taken from a calibration pass without quantization: the device's selection over
+    the score arrays equals the oracle's over their union, and the layers end up with different FP8
+    fractions.  The operands of the first two products are made so that the products of the STORED values
+    have no rounding in any order of summation (checked here on the oracle's values): every stage's
+    integers -- codes, block scales, decisions -- and scores then equal the oracle's bit for bit, and the
+    last stage's FP32 results agree within the product's tolerance."""
+    M, K1, N1, N2, N3, seed, p = 136, 128, 128, 256, 72, 42, 0.2
+    x1, w1, w2 = synth.exact_sum_operand(M, K1, seed, 1), synth.exact_sum_operand(N1, K1, seed, 2), synth.exact_sum_operand(N2, N1, seed, 3)
+    w3, w3ref = _to_dev_bf16(synth.weights(N3, N2 // 2, seed, 7))
+    ones1, ones2, ones3 = np.ones(K1, np.float32), np.ones(N1, np.float32), np.ones(N2 // 2, np.float32)
+    # calibration pass (no quantization) and per-tensor sensitivities: smaller where the values are larger
+    y1c = (x1.astype(np.float64) @ w1.astype(np.float64).T).astype(np.float32)
+    hc = orc.gate_columns((y1c.astype(np.float64) @ w2.astype(np.float64).T).astype(np.float32))
+    f1 = (synth.fisher_per_channel(K1, seed, 4) * np.float32(2000.0)).astype(np.float32)
+    f2 = (synth.fisher_per_channel(N1, seed, 5) * np.float32((np.abs(x1).max() / np.abs(y1c).max()) ** 2 * 0.002)).astype(np.float32)
+    fh = (synth.fisher_per_channel(N2 // 2, seed, 6) * np.float32((np.abs(x1).max() / np.abs(hc).max()) ** 2 * 1500.0)).astype(np.float32)
+    S1, S2 = 1.0, float(2.0 ** np.ceil(np.log2(np.abs(y1c).max() / 448.0)))
+    Sh, S3 = float(np.float32(np.abs(hc).max()) / np.float32(448.0)), float(synth.default_tensor_scale(w3ref))
+    # ---- oracle: thresholds, then the quantized chain
+    sx = [orc.quantize(t, f, np.inf, S)["scores"] for t, f, S in ((x1, f1, S1), (y1c, f2, S2), (hc, fh, Sh))]
+    sw = [orc.quantize(t, f, np.inf, S)["scores"] for t, f, S in ((w1, ones1, 1.0), (w2, ones2, 1.0), (w3ref, ones3, S3))]
+    Tx = orc.threshold(np.concatenate([t.reshape(-1) for t in sx]), p)
+    Tw = orc.threshold(np.concatenate([t.reshape(-1) for t in sw]), p)
+    deq = lambda q: orc.dequantize(q["codes"], q["scales"], q["mask"])
+    q1x, q1w = orc.quantize(x1, f1, Tx, S1), orc.quantize(w1, ones1, Tw, 1.0)
+    assert _exactly_summable(deq(q1x), deq(q1w))
+    y1 = orc.gemm(deq(q1x), S1, deq(q1w), 1.0)[0]
+    y1_32 = y1.astype(np.float32)
+    assert np.array_equal(y1_32.astype(np.float64), y1)
+    q2x, q2w = orc.quantize(y1_32, f2, Tx, S2), orc.quantize(w2, ones2, Tw, 1.0)
+    assert _exactly_summable(deq(q2x), deq(q2w))
+    y2 = orc.gemm(deq(q2x), S2, deq(q2w), 1.0)[0]
+    y2_32 = y2.astype(np.float32)
+    assert np.array_equal(y2_32.astype(np.float64), y2)
+    want_h = orc.quantize(orc.gate_columns(y2_32), fh, Tx, Sh)
+    q3w = orc.quantize(w3ref, ones3, Tw, S3)
+    z_want, z_tol = orc.gemm(deq(want_h), Sh, deq(q3w), S3)
+    fractions = [float(q["mask"].mean()) for q in (q1x, q2x, want_h)]
+    assert fractions[0] > 0.05 and fractions[2] > 0.05 and len({round(f, 3) for f in fractions}) == 3
+    # ---- device: the same thresholds from the same calibration tensors, then the chain on its own outputs
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    x1d, w1d, w2d, f1d, f2d, fhd = up(x1), up(w1), up(w2), up(f1), up(f2), up(fh)
+    o1d, o2d, o3d = up(ones1), up(ones2), up(ones3)
+    dsx = [fgmp.quantize_activations(t, f, np.inf, S, want_scores=True)[1]
+           for t, f, S in ((x1d, f1d, S1), (up(y1c), f2d, S2), (up(hc), fhd, Sh))]
+    dsw = [fgmp.quantize_weights(t, f, np.inf, S, want_scores=True)[1] for t, f, S in ((w1d, o1d, 1.0), (w2d, o2d, 1.0), (w3, o3d, S3))]
+    assert fgmp.threshold_for_fraction_multi(dsx, p) == Tx and fgmp.threshold_for_fraction_multi(dsw, p) == Tw
+    pW1, pW2, pW3 = fgmp.quantize_weights(w1d, o1d, Tw, 1.0), fgmp.quantize_weights(w2d, o2d, Tw, 1.0), fgmp.quantize_weights(w3, o3d, Tw, S3)
+    Y1 = fgmp.quant_gemm_fused(x1d, f1d, Tx, S1, pW1)
+    assert np.array_equal(Y1.cpu().numpy(), y1_32), "stage 1"
+    pH, h_scores = fgmp.quant_gemm_fused_packed_out(Y1, f2d, Tx, S2, pW2, fhd, Tx, Sh, want_scores=True,
+                                                     epilogue=fgmp.EPILOGUE_SILU_GATE)
+    _assert_quant_equal(pH, h_scores, want_h, "stage 2 (gated, packed output)")
+    Z = fgmp.gemm(pH, pW3)
+    assert np.all(np.abs(Z.cpu().numpy().astype(np.float64) - z_want) <= z_tol), "stage 3"
+    got_fr = [fgmp.packed_info(fgmp.quantize_activations(x1d, f1d, Tx, S1))["n_fp8_blocks"] / (M * K1 // 16),
+              fgmp.packed_info(pH)["n_fp8_blocks"] / (M * (N2 // 2) // 16)]
+    assert got_fr == [fractions[0], fractions[2]]
+
+
 # ------------------------------------------------------------------ output-side quantization (Sec. 4.2)
 
 def _exact_product_case(M, K, N, seed):
