@@ -59,6 +59,59 @@ def bytes_per_block(p: float) -> float:
     return (1.0 - p) * 9.0 + p * 16.0 + 0.125
 
 
+def single_case(args, torch, fgmp, synth, dev, dev_bf16, timed) -> int:
+    """One kernel, one shape, HBM-cold (the launches rotate over copies that exceed the Infinity Cache)."""
+    parts = args.case.split(":")
+    if parts[0] == "quantizer":
+        Mq, Kq = 16384, 8192
+        xqd, xqbits = dev_bf16(synth.activations(Mq, Kq, 0, 11))
+        sq = float(synth.default_tensor_scale(synth.bf16_bits_to_f32(xqbits)))
+        del xqbits
+        fq = torch.from_numpy(synth.fisher_per_channel(Kq, 0, 12)).to(dev)
+        _, sc = fgmp.quantize_activations(xqd, fq, float("inf"), sq, want_scores=True)
+        Tq = fgmp.threshold_for_fraction(sc, P_FP8)
+        del sc
+        pq = fgmp.quantize_activations(xqd, fq, Tq, sq)
+        ms = timed(lambda: fgmp.quantize_activations(xqd, fq, Tq, sq, out=pq), args.steps, args.warmup)
+        nbytes = Mq * Kq * 2 + (Mq * Kq // 16) * bytes_per_block(P_FP8)
+    elif parts[0] == "decode" and len(parts) == 3:
+        shapes = dict(synth.LLAMA2_7B)
+        shapes["fc1_70b"] = synth.LLAMA2_70B_FC1
+        Kd, Nd = shapes[parts[1]]
+        Md = int(parts[2])
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(20)
+        wq = torch.empty((Nd, Kd), dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02, generator=gen)
+        swq = float(wq.abs().max().float()) / 448.0
+        fwq = torch.from_numpy(synth.fisher_per_channel(Kd, 0, 21)).to(dev)
+        _, scq = fgmp.quantize_weights(wq, fwq, float("inf"), swq, want_scores=True)
+        Twq = fgmp.threshold_for_fraction(scq, P_FP8)
+        del scq
+        pWd = fgmp.quantize_weights(wq, fwq, Twq, swq)
+        del wq
+        ncopies = int(600e6 // pWd.buf.numel()) + 1
+        pool = [fgmp.Packed(pWd.buf.clone(), Nd, Kd) for _ in range(ncopies)]
+        xk, xkb = dev_bf16(synth.activations(Md, Kd, 0, 23))
+        sxk = float(synth.default_tensor_scale(synth.bf16_bits_to_f32(xkb)))
+        fxk = torch.from_numpy(synth.fisher_per_channel(Kd, 0, 22)).to(dev)
+        Yd = torch.empty((Md, Nd), dtype=torch.float32, device=dev)
+        wsd = fgmp.new_workspace(fgmp.workspace_bytes(Md, Nd, Kd), dev)
+        it = [0]
+
+        def call():
+            fgmp.quant_gemm_fused(xk, fxk, 1e-3, sxk, pool[it[0] % ncopies], out=Yd, workspace=wsd)
+            it[0] += 1
+        ms = timed(call, args.steps, args.warmup)
+        nbytes = Nd * Kd // 16 * bytes_per_block(P_FP8) + Md * Kd * 2 + Md * Nd * 4
+    else:
+        print(f"bench.py: unknown --case {args.case}", file=sys.stderr)
+        return 2
+    print(json.dumps({"case": args.case, "us_per_launch": round(ms * 1e3, 2), "algorithmic_bytes": int(nbytes),
+                      "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}),
+          flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +121,9 @@ def main() -> int:
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip the FP8-fraction sweep at the Llama-2-70B FC1 shape (configs[4]; a few GB, ~1 min)")
+    ap.add_argument("--case", default=None,
+                    help="run ONE kernel-level case in a loop of --steps launches and print its time (what the profiles/ "
+                         "summaries of single kernels are made with): decode:<qkv|o|fc1|fc2|fc1_70b>:<M>, or quantizer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -105,6 +161,9 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters  # ms per call
+
+    if args.case:
+        return single_case(args, torch, fgmp, synth, dev, dev_bf16, timed)
 
     # ------------------------------------------------------------ workload (configs[1])
     M, K, N = 4096, 4096, 12288
