@@ -47,8 +47,8 @@ namespace fgmp {
 
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kStWaves = 12;                 // waves per workgroup: three per SIMD, up to 170 vector registers each
-constexpr int kStThreads = 64 * kStWaves;
+constexpr int kStMaxWaves = 16;              // most waves a workgroup can have (the kernels take the count as a parameter; 12 -- three
+                                             // per SIMD, up to 170 vector registers each -- is what the host chooses)
 constexpr int kStRing = 4;                   // K-tiles in flight per wave (a compute unit keeps about 32 KB of requests in flight: more only block the waves that issue them)
 constexpr int kStEarly = 4;                  // K-tiles whose planes L / S are requested before the activations are dealt with (<= kStRing)
 constexpr int kStHLead = 2;                  // plane-H entries are requested this many tiles ahead (steady state)
@@ -99,7 +99,7 @@ struct StreamArgs {
 // (a build with FGMP_STREAM_TIMING -- none of the shipped variants -- records when each wave passes the
 // kernel's phases, behind the call's scratch: the tool the phase times quoted in the design notes came from)
 #ifdef FGMP_STREAM_TIMING
-#define ST_STAMP(i) do { if (lane == 0) a.dbg[((size_t)wg * kStWaves + wave) * 8 + (i)] = wall_clock64(); } while (0)
+#define ST_STAMP(i) do { if (lane == 0) a.dbg[((size_t)wg * kStMaxWaves + wave) * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define ST_STAMP(i) do { } while (0)
 #endif
@@ -340,13 +340,14 @@ static_assert(st_step_wait(0) == 3 && st_step_wait(1) == 5 && st_step_wait(2) ==
 static_assert(st_step_wait(4) == 6 && st_step_wait(5) == 6 && st_step_wait(6) == 6 && st_step_wait(7) == 6, "steady state");
 static_assert(st_step_wait(8) == 6 && st_step_wait(9) == 6 && st_step_wait(10) == 6 && st_step_wait(11) == 6, "steady state");
 
-// MT: 16-row groups of X (1: M <= 16, 2: M <= 32).  kXR: rows of X kept in LDS (8, 16 or 32; rows of the
+// MT: 16-row groups of X (1: M <= 16, 2: M <= 32).  kXR: rows of X kept in LDS (1, 8, 16 or 32; rows of the
 // MFMA operand beyond them alias rows there are -- they only feed output rows that are never stored).
 // kSrc: 0 bf16 input, 1 fp32 input, 2 packed activations.
-template <int MT, int kXR, int kSrc>
-__global__ __launch_bounds__(kStThreads) void gemm_stream_kernel(StreamArgs a)
+template <int kStWaves, int MT, int kXR, int kSrc>
+__global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a)
 {
-    static_assert(kXR == 8 || kXR == 16 * MT, "rows of X in LDS");
+    constexpr int kStThreads = 64 * kStWaves;
+    static_assert(kXR == 1 || kXR == 8 || kXR == 16 * MT, "rows of X in LDS");
     __shared__ __attribute__((aligned(16))) _Float16 xs[kStXCap];
     __shared__ float4_t red[kStWaves][MT][64];
     __shared__ uint32_t hw[4];   // what the kernel needs of the weights' header
@@ -726,7 +727,7 @@ __global__ __launch_bounds__(kStThreads) void gemm_stream_kernel(StreamArgs a)
 
 struct StreamPlan {
     bool ok;
-    int mt, xr, P_g, n_slots, tiles_gpart, kp_in, tiles_in, gpr, rounds, n_groups, grid;
+    int waves, mt, xr, P_g, n_slots, tiles_gpart, kp_in, tiles_in, gpr, rounds, n_groups, grid;
     size_t total;   // scratch: the partial sums
     uint32_t partial_bytes;
 };
@@ -741,7 +742,9 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t K)
     if (M < 1 || M > 32 || lw.total_bytes >= kLimit) return p;
     if (lw.n_rt % 2 != 0) return p;   // (a row group is two row-tiles)
     p.mt = M <= 16 ? 1 : 2;
-    p.xr = M <= 8 ? 8 : 16 * p.mt;
+    p.waves = 12;   // (measured: 8 and 16 waves per workgroup both run 5-15% slower on the Llama-2 shapes)
+    const int kStThreads = 64 * p.waves, kStWaves = p.waves;
+    p.xr = M == 1 ? 1 : M <= 8 ? 8 : 16 * p.mt;   // (one token: a single row, whatever K -- no part of K goes to another workgroup for the LDS's sake)
     const int n_kt = (int)lw.n_kt;
     // parts of K across workgroups: as few as let a part's rows fit the LDS and let every thread do with
     // one K-block of at most kStXRows rows
@@ -791,7 +794,7 @@ size_t gemm_stream_scratch_bytes(int64_t M, int64_t N, int64_t K)
 {
     const StreamPlan p = stream_plan(M, N, K);
 #ifdef FGMP_STREAM_TIMING
-    return p.ok && kUseHwCvt ? p.total + (size_t)kStCus * kStWaves * 64 : 0;
+    return p.ok && kUseHwCvt ? p.total + (size_t)kStCus * kStMaxWaves * 64 : 0;
 #else
     return p.ok && kUseHwCvt ? p.total : 0;
 #endif
@@ -799,10 +802,11 @@ size_t gemm_stream_scratch_bytes(int64_t M, int64_t N, int64_t K)
 
 template <int kSrc> static void launch_stream(const StreamPlan &p, const StreamArgs &a, hipStream_t st)
 {
-    const dim3 grid((unsigned)p.grid), block(kStThreads);
-    if (p.mt == 1 && p.xr == 8) hipLaunchKernelGGL((gemm_stream_kernel<1, 8, kSrc>), grid, block, 0, st, a);
-    else if (p.mt == 1) hipLaunchKernelGGL((gemm_stream_kernel<1, 16, kSrc>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((gemm_stream_kernel<2, 32, kSrc>), grid, block, 0, st, a);
+    const dim3 grid((unsigned)p.grid), block((unsigned)(64 * p.waves));
+    if (p.xr == 1) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 1, kSrc>), grid, block, 0, st, a);
+    else if (p.mt == 1 && p.xr == 8) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 8, kSrc>), grid, block, 0, st, a);
+    else if (p.mt == 1) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 16, kSrc>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((gemm_stream_kernel<12, 2, 32, kSrc>), grid, block, 0, st, a);
 }
 
 // src: 0 bf16 X, 1 fp32 X (quantized in the kernel with fisher / T / S), 2 packed X.
@@ -833,7 +837,7 @@ fgmp_status_t gemm_stream(int src, const void *X, int64_t ldx, const float *fish
     a.P_g = p.P_g; a.n_slots = p.n_slots; a.tiles_gpart = p.tiles_gpart; a.kp_in = p.kp_in;
     a.tiles_in = p.tiles_in; a.gpr = p.gpr; a.rounds = p.rounds; a.n_groups = p.n_groups;
     a.groups_q = p.n_groups / p.n_slots; a.groups_r = p.n_groups % p.n_slots;
-    a.rows_par = kStThreads / (p.tiles_gpart * kTileBlocks);
+    a.rows_par = 64 * p.waves / (p.tiles_gpart * kTileBlocks);
     a.by_P_g = stream_div(p.P_g); a.by_kp_in = stream_div(p.kp_in); a.by_tiles_in = stream_div(p.tiles_in);
     a.by_gpr = stream_div(p.gpr); a.by_pb = stream_div(p.tiles_gpart * kTileBlocks);
 #ifdef FGMP_STREAM_TIMING
