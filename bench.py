@@ -379,16 +379,16 @@ def main() -> int:
                     "frac_hbm_peak": round(dbytes / (ms_d * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
                     "frac_of_measured_copy": round(dbytes / (ms_d * 1e-3) / 1e9 / copy_gbps, 4),
                     "us_gemm_from_packed_x": round(ms_g * 1e3, 2), "packed_w_bytes": used}
-                if name == "qkv":
-                    # the same steps captured in one HIP graph (a step per weight copy) and replayed: what a
-                    # serving loop that is bound by launch overhead on the host would run
-                    graph = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(graph):
-                        for cpy in pool:
-                            fgmp.quant_gemm_fused(xmd, fxk, 1e-3, sx, cpy, out=Yd, workspace=wsd)
-                    ms_graph = timed(graph.replay, 10, 3) / ncopies
-                    dec[f"{name}_K{Kd}_N{Nd}_M{Md}"]["us_per_step_in_hip_graph"] = round(ms_graph * 1e3, 2)
-                    del graph
+                # the same steps captured in one HIP graph (a step per weight copy) and replayed: what a serving
+                # loop runs that must not be bound by the host's launch path (the eager loop above issues one
+                # Python call per step; steps shorter than that call are host-bound there)
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for cpy in pool:
+                        fgmp.quant_gemm_fused(xmd, fxk, 1e-3, sx, cpy, out=Yd, workspace=wsd)
+                ms_graph = timed(graph.replay, 10, 3) / ncopies
+                dec[f"{name}_K{Kd}_N{Nd}_M{Md}"]["us_per_step_in_hip_graph"] = round(ms_graph * 1e3, 2)
+                del graph
             del pool
         extra["decode_hbm_cold"] = dec
         # kernel-level entries beside the dominant kernel's: both are bound by HBM; bytes are the algorithmic
