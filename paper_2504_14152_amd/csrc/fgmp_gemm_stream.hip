@@ -237,7 +237,10 @@ __device__ __forceinline__ void st_load_t(StreamSlot &s, __amdgpu_buffer_rsrc_t 
 }
 __device__ __forceinline__ void st_load_ls(StreamSlot &s, __amdgpu_buffer_rsrc_t r, uint32_t vL, uint32_t vS, uint32_t tile)
 {
-    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(s.l) : "v"(vL), "s"(r), "s"(tile * (kTileSlots * 8u)));
+    // (plane L is read once and is most of the traffic: a streaming load -- it does not displace the small planes'
+    // lines, which neighbouring tiles share, from the caches; 6-7% on the Llama-2 shapes.  The same hint on the
+    // other planes' loads costs what it gains here.)
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen nt" : "=v"(s.l) : "v"(vL), "s"(r), "s"(tile * (kTileSlots * 8u)));
     asm volatile("buffer_load_ushort %0, %1, %2, %3 offen" : "=v"(s.s) : "v"(vS), "s"(r), "s"(tile * (uint32_t)kTileSlots));
 }
 __device__ __forceinline__ void st_load_h(StreamSlot &s, __amdgpu_buffer_rsrc_t r, uint32_t off)
