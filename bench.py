@@ -397,6 +397,37 @@ def main() -> int:
                 ms_graph = timed(graph.replay, 10, 3) / ncopies
                 dec[f"{name}_K{Kd}_N{Nd}_M{Md}"]["us_per_step_in_hip_graph"] = round(ms_graph * 1e3, 2)
                 del graph
+                if name in ("qkv", "fc1"):
+                    # the same step with its results quantized and packed inside the launch (Sec. 4.2), against
+                    # the FP32 step followed by the standalone quantizer (10% of the result blocks FP8)
+                    fnd = torch.from_numpy(synth.fisher_per_channel(Nd, 0, 24)).to(dev)
+                    call()
+                    s_yd = float(Yd.abs().max()) / 448.0
+                    _, scy = fgmp.quantize_activations(Yd, fnd, float("inf"), s_yd, want_scores=True)
+                    T_yd = fgmp.threshold_for_fraction(scy, P_FP8)
+                    wsp = fgmp.new_workspace(fgmp.workspace_bytes_packed_out(Md, Nd, Kd), dev)
+                    pYd = fgmp.quant_gemm_fused_packed_out(xmd, fxk, 1e-3, sx, pool[0], fnd, T_yd, s_yd, workspace=wsp)
+                    pYq = fgmp.quantize_activations(Yd, fnd, T_yd, s_yd)
+
+                    def call_packed():   # one launch: the step quantizes its own results
+                        fgmp.quant_gemm_fused_packed_out(xmd, fxk, 1e-3, sx, pool[it[0] % ncopies], fnd, T_yd, s_yd,
+                                                         out=pYd, workspace=wsp, epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+                        it[0] += 1
+
+                    def call_then_quantize():   # two launches: FP32 results, then the standalone quantizer
+                        call()
+                        fgmp.quantize_activations(Yd, fnd, T_yd, s_yd, out=pYq)
+                    entry = dec[f"{name}_K{Kd}_N{Nd}_M{Md}"]
+                    entry["packed_out"] = {"us_one_launch": round(timed(call_packed, 40, 5) * 1e3, 2),
+                                           "us_two_launches": round(timed(call_then_quantize, 40, 5) * 1e3, 2)}
+                    for tag, fn in (("us_one_launch_in_hip_graph", call_packed), ("us_two_launches_in_hip_graph", call_then_quantize)):
+                        it[0] = 0
+                        graph = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(graph):
+                            for _ in range(ncopies):
+                                fn()
+                        entry["packed_out"][tag] = round(timed(graph.replay, 10, 3) / ncopies * 1e3, 2)
+                        del graph
             del pool
         extra["decode_hbm_cold"] = dec
         # kernel-level entries beside the dominant kernel's: both are bound by HBM; bytes are the algorithmic

@@ -66,8 +66,9 @@ typedef enum { FGMP_F32 = 0, FGMP_BF16 = 1 } fgmp_dtype_t;
 typedef enum { FGMP_SCORE_NVFP4_ERROR = 0, FGMP_SCORE_DELTA = 1 } fgmp_score_mode_t;
 
 /* Elementwise operator between the product and the output quantizer of
- * fgmp_quant_gemm_fused_packed_out_ex (see there). */
-typedef enum { FGMP_EPILOGUE_NONE = 0, FGMP_EPILOGUE_SILU_GATE = 1 } fgmp_epilogue_t;
+ * fgmp_quant_gemm_fused_packed_out_ex (see there); FGMP_EPILOGUE_ONE_LAUNCH is a flag that may be ORed
+ * to an operator. */
+typedef enum { FGMP_EPILOGUE_NONE = 0, FGMP_EPILOGUE_SILU_GATE = 1, FGMP_EPILOGUE_ONE_LAUNCH = 0x100 } fgmp_epilogue_t;
 
 /* Host-side summary of a packed tensor (fgmp_packed_info). */
 typedef struct {
@@ -206,7 +207,13 @@ fgmp_status_t fgmp_quant_gemm_fused_ex(const void *X, fgmp_dtype_t dt, int64_t M
  * compared with `threshold_y` and stored as FP8 or NVFP4 in `packed_Y`, a packed M x N activation
  * tensor (tensor scale `scale_y`) that the next layer's fgmp_gemm consumes.  The values that are
  * quantized are exactly the FP32 numbers fgmp_quant_gemm_fused would have written.  For shapes that
- * run on the prefill kernel this happens in its epilogue; small M stage the FP32 results in the workspace.
+ * run on the prefill kernel this happens in its epilogue; smaller M stage the FP32 results in the
+ * workspace and launch the standalone quantizer.  A decode step (M <= 32) can also do it inside its one
+ * launch (FGMP_EPILOGUE_ONE_LAUNCH of the _ex form): the wave that holds the final sums of 16 output
+ * columns quantizes them, and the eight such waves behind one 128-column tile of packed_Y settle the
+ * tile's mask word and plane-H order through a counter in the workspace's control region.  That chain of
+ * memory round trips at the end of the launch measured 1-8 us slower than the second launch, so it is
+ * not the default; the packed tensor is the same bit for bit either way.
  *   fisher_n   N FP32 sensitivities; N % 16 == 0
  *   packed_Y   out, packed_Y_bytes >= fgmp_packed_bytes(M, N); scores_y nullable, M*N/16 FP32
  *   workspace  >= fgmp_workspace_bytes_packed_out(M, N, K)
@@ -231,6 +238,9 @@ fgmp_status_t fgmp_quant_gemm_fused_packed_out(const void *X, fgmp_dtype_t dt, i
  * own: E(x) for x clamped to [-87, 88] is p * 2^n with n = rint(x * log2 e), r = (x - n * 0.693359375)
  * - n * (ln 2 - 0.693359375) and p the degree-7 Taylor polynomial of e^r by Horner's rule;
  * h = (g / (1 + E(-g))) * u with a correctly rounded division (within 3 ulp of the exact value).
+ * `epilogue | FGMP_EPILOGUE_ONE_LAUNCH` (with FGMP_EPILOGUE_NONE): a decode step quantizes its results
+ * inside its launch whenever the one-launch kernel handles the shape (nothing is staged; a single kernel
+ * per layer for callers who count launches); shapes that no quantizing epilogue covers are staged as before.
  *   N          N % 64 == 0 with the gate; fisher_n, scores_y and packed_Y then refer to N/2 columns
  *   workspace  >= fgmp_workspace_bytes_packed_out_ex(M, N, K, epilogue)
  * Other arguments and errors as fgmp_quant_gemm_fused_packed_out; an unknown `epilogue` is

@@ -144,10 +144,11 @@ fgmp_status_t fgmp_quant_gemm_fused_packed_out(const void *X, fgmp_dtype_t dt, i
 
 size_t fgmp_workspace_bytes_packed_out_ex(int64_t M, int64_t N, int64_t K, fgmp_epilogue_t epilogue)
 {
-    if (epilogue != FGMP_EPILOGUE_NONE && epilogue != FGMP_EPILOGUE_SILU_GATE) return 0;
-    const int64_t n_unit = epilogue == FGMP_EPILOGUE_SILU_GATE ? 64 : kBlock;
+    const int op = (int)epilogue & ~(int)FGMP_EPILOGUE_ONE_LAUNCH;
+    if (op != FGMP_EPILOGUE_NONE && op != FGMP_EPILOGUE_SILU_GATE) return 0;
+    const int64_t n_unit = op == FGMP_EPILOGUE_SILU_GATE ? 64 : kBlock;
     if (M <= 0 || N <= 0 || K <= 0 || K % kBlock != 0 || N % n_unit != 0) return 0;
-    return gemm_workspace_bytes_packed_out(M, N, K, (int)epilogue);
+    return gemm_workspace_bytes_packed_out(M, N, K, op);
 }
 
 fgmp_status_t fgmp_quant_gemm_fused_packed_out_ex(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,

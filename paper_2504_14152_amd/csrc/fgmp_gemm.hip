@@ -346,20 +346,24 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
     if (((uintptr_t)workspace | (uintptr_t)packed_W | (uintptr_t)Y) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
     // (the one-launch kernel addresses X with 32-bit byte offsets)
     const bool x_fits = ldx > 0 && ldx < (int64_t)0xFFFFFF00 / (M * 4);
-    const bool stream = score_mode == FGMP_SCORE_NVFP4_ERROR && pack_out == nullptr && x_fits && gemm_stream_applies(M, N, K);
-    if (workspace_bytes < (stream ? quant_gemm_workspace_need(M, N, K) : gemm_workspace_bytes(M, N, K)))
+    // (the decode step quantizes its own results where the caller asks for it)
+    const bool stream_pack = pack_out != nullptr && !pack_out->gate && pack_out->one_launch && gemm_stream_packs(M, N, K);
+    const bool stream = score_mode == FGMP_SCORE_NVFP4_ERROR && (pack_out == nullptr || stream_pack) && x_fits && gemm_stream_applies(M, N, K);
+    if (workspace_bytes < (stream ? (pack_out ? kWsCtrlRegion + gemm_stream_pack_scratch_bytes(M, N, K) : quant_gemm_workspace_need(M, N, K))
+                                  : gemm_workspace_bytes(M, N, K)))
         return FGMP_ERR_BUFFER_TOO_SMALL;
     char *ws = static_cast<char *>(workspace) + kWsCtrlRegion;
     if (stream) {
-        // decode shapes: one launch quantizes the activation rows and streams the weights
-        if (!X || !fisher_k || !Y) return FGMP_ERR_INVALID_ARG;
+        // decode shapes: one launch quantizes the activation rows and streams the weights (and, with
+        // `pack_out`, quantizes and packs the results)
+        if (!X || !fisher_k || (!Y && !pack_out)) return FGMP_ERR_INVALID_ARG;
         if (dt != FGMP_F32 && dt != FGMP_BF16) return FGMP_ERR_UNSUPPORTED;
         if (!(scale_x > 0.0f) || !(scale_x < INFINITY) || threshold != threshold) return FGMP_ERR_INVALID_ARG;
         const int64_t esz = dt == FGMP_F32 ? 4 : 2;
         if (ldx < K) return FGMP_ERR_BAD_SHAPE;
         if (((uintptr_t)X | (uintptr_t)fisher_k) % 16 != 0 || (ldx * esz) % 16 != 0) return FGMP_ERR_BAD_ALIGN;
         return gemm_stream(dt == FGMP_F32 ? 1 : 0, X, ldx, fisher_k, threshold, scale_x, nullptr, M, packed_W, N, K, Y, ldy,
-                           workspace, ws, st);
+                           workspace, ws, st, pack_out);
     }
     const bool in_kernel_prefill = !gemm_skinny_applies(M, N, K) && mixed_kernel_applies(N, K) && kUseHwCvt;
     if (pack_out != nullptr && !in_kernel_prefill) return FGMP_ERR_UNSUPPORTED;   // the caller falls back
@@ -403,8 +407,10 @@ fgmp_status_t quant_gemm(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, i
 }
 
 // Fused call whose results are quantized and packed instead of stored as FP32 (Sec. 4.2).  Prefill
-// shapes do it in the GEMM's epilogue; other shapes (and the two-pass path) write FP32 results to the
-// workspace and run the standalone quantizer over them -- the same arithmetic on the same values.
+// shapes do it in the GEMM's epilogue, decode steps (M <= 32) inside their one launch when asked to
+// (FGMP_EPILOGUE_ONE_LAUNCH); otherwise, for other shapes, the gated epilogue at decode sizes and the
+// two-pass path, the FP32 results go to the workspace and the standalone quantizer runs over them -- the
+// same arithmetic on the same values.
 size_t gemm_workspace_bytes_packed_out(int64_t M, int64_t N, int64_t K, int epilogue)
 {
     // FP32 staging of the product for the shapes whose epilogue cannot quantize, and of the gated values
@@ -433,6 +439,8 @@ fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, i
 {
     if (!fisher_n || !packed_Y || !workspace) return FGMP_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0 || K <= 0) return FGMP_ERR_INVALID_ARG;
+    const bool one_launch = (epilogue & FGMP_EPILOGUE_ONE_LAUNCH) != 0;
+    epilogue &= ~(int)FGMP_EPILOGUE_ONE_LAUNCH;
     if (epilogue != FGMP_EPILOGUE_NONE && epilogue != FGMP_EPILOGUE_SILU_GATE) return FGMP_ERR_INVALID_ARG;
     if (!(scale_y > 0.0f) || !(scale_y < INFINITY) || threshold_y != threshold_y) return FGMP_ERR_INVALID_ARG;
     const bool gate = epilogue == FGMP_EPILOGUE_SILU_GATE;
@@ -452,9 +460,11 @@ fgmp_status_t quant_gemm_packed_out(const void *X, fgmp_dtype_t dt, int64_t M, i
     po.S = scale_y;
     po.scores = scores_y;
     po.gate = gate ? 1 : 0;
+    po.one_launch = one_launch ? 1 : 0;
     const size_t base_bytes = gemm_workspace_bytes(M, N, K);
+    // (the whole workspace: the one-launch decode step keeps its row groups' decisions behind its partial sums)
     fgmp_status_t rc = quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, nullptr, N, workspace,
-                                  base_bytes, st, FGMP_SCORE_NVFP4_ERROR, &po);
+                                  workspace_bytes, st, FGMP_SCORE_NVFP4_ERROR, &po);
     if (rc != FGMP_ERR_UNSUPPORTED) return rc;
     float *Yf = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up(base_bytes, 256));
     rc = quant_gemm(X, dt, M, K, ldx, fisher_k, threshold, scale_x, packed_W, N, Yf, N, workspace, base_bytes, st,

@@ -434,8 +434,8 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
         // free now) so that a lane owns one output block: (row = lane % 32, 16 columns = lane / 32).  The
         // block goes through the quantizer's arithmetic; codes, scale bytes and FP8 upper halves are
         // written by the lane, the mask words of the 64 packed tiles this workgroup covers are gathered
-        // in LDS.  Plane-H entries sit at the block's own slot (any unique index within the tile's
-        // 64-entry region is valid for a strided tensor).
+        // in LDS; the FP8 upper halves go to the block's own slot of the tile's plane-H region first and to
+        // their final places once the masks are complete (below).
         constexpr int kTStride = 36;   // floats per transposed row: 16-byte aligned rows, staggered banks
         __syncthreads();
         float *tbuf = reinterpret_cast<float *>(&lds[0][0][0]) + wave * (32 * kTStride);
@@ -496,20 +496,35 @@ __global__ __launch_bounds__(kWM *kWN * 64, 1) void gemm_mixed_kernel(const _Flo
                         encode_fp8_block<true, true>(rr, c);
                         lword = make_uint2(c[0], c[1]);
                         po.out.H[at] = make_uint2(c[2], c[3]);
-                        sbyte = (uint32_t)slot;
                         atomicOr(&m_lds[(row_l >> 3) * 2 + (col_l >> 7)], 1ull << slot);
+                    } else {
+                        po.out.S[at] = (uint8_t)sbyte;
                     }
                     po.out.L[at] = lword;
-                    po.out.S[at] = (uint8_t)sbyte;
                 }
             }
+        __builtin_amdgcn_s_waitcnt(0);   // this wave's stores have reached the L2
         __syncthreads();
-        if (tid < 64) {
-            const int64_t rt = tm * (kBM / kTileRows) + (tid >> 1), kt = tn * (kOutBN / kTileK) + (tid & 1);
-            if (rt < ly.n_rt && kt < ly.n_kt && (tid & 1) < kOutBN / kTileK) {
+        // A block's plane-H entry belongs at the number of FP8 slots before it in its tile (readers may take
+        // that from the mask), and that number is its plane-S byte: known now that the tile's mask word is
+        // complete.  One wave per tile, lane = slot, moves the entries from the blocks' own slots (every
+        // entry is in a register before the first one is stored again: a store waits for its data, i.e. for
+        // the load instruction as a whole).
+        for (int q = wave; q < 64; q += kWaves) {
+            const int64_t rt = tm * (kBM / kTileRows) + (q >> 1), kt = tn * (kOutBN / kTileK) + (q & 1);
+            if (rt < ly.n_rt && kt < ly.n_kt && (q & 1) < kOutBN / kTileK) {
+                const unsigned long long mask = m_lds[q];
                 const int64_t tile = rt * ly.n_kt + kt;
-                po.out.M[tile] = m_lds[tid];
-                po.out.T[tile] = (uint32_t)(tile * kTileSlots);
+                if ((mask >> lane) & 1ull) {
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    const uint2 e = po.out.H[tile * kTileSlots + lane];
+                    po.out.H[tile * kTileSlots + rank] = e;
+                    po.out.S[tile * kTileSlots + lane] = (uint8_t)rank;
+                }
+                if (lane == 0) {
+                    po.out.M[tile] = mask;
+                    po.out.T[tile] = (uint32_t)(tile * kTileSlots);
+                }
             }
         }
         // the header: by the workgroup that completes the first tile of the launch order

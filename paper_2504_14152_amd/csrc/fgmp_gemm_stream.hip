@@ -82,6 +82,15 @@ struct StreamArgs {
     float *Y;
     int64_t ldy;
     int M, N, nb_x;             // nb_x: K / 16
+    // ... or, quantized and packed, as the next product's activations (Sec. 4.2): a strided M x N tensor
+    void *y_packed;
+    uint32_t y_bytes, y_off_L, y_off_S, y_off_M, y_off_T, y_off_H;
+    int y_n_kt;
+    const float *fisher_y;      // N sensitivities (input channels of the next layer)
+    float T_y, S_y;
+    float *scores_y;            // nullable, M x N / 16
+    uint32_t *dec;              // [row group] which of the M blocks it produced are FP8 (bit m), until the tile's mask word is made
+    uint32_t *uctr;             // one arrival counter per 8 row groups (= one K-tile of the packed result); zero between calls
     // scratch
     uint32_t *gctr;             // one arrival counter per row group (P_g > 1); zero between calls
     uint32_t x_bytes;           // extent of the input X
@@ -346,7 +355,17 @@ static_assert(st_step_wait(8) == 6 && st_step_wait(9) == 6 && st_step_wait(10) =
 // MT: 16-row groups of X (1: M <= 16, 2: M <= 32).  kXR: rows of X kept in LDS (1, 8, 16 or 32; rows of the
 // MFMA operand beyond them alias rows there are -- they only feed output rows that are never stored).
 // kSrc: 0 bf16 input, 1 fp32 input, 2 packed activations.
-template <int kStWaves, int MT, int kXR, int kSrc>
+// kPack: the results leave quantized and packed instead of as FP32 (Sec. 4.2: the quantization unit sits behind
+// the accumulators).  A 16-column block of one output row is exactly one row group's result, so the wave that
+// holds a row group's final sums scores and encodes its M blocks itself (the quantizer's own block arithmetic) and
+// writes their plane-L words, scale bytes and scores.  What a block's neighbours decide matters only for the
+// tile's mask word and for the place of its FP8 upper half among the tile's plane-H entries: a tile of the
+// result spans 8 row groups, which belong to different waves and workgroups.  Each row group leaves its M
+// decisions (one word) and its FP8 upper halves (at the block's own slot of the tile's 64-entry region) with
+// accesses that are coherent across the chip and bumps the counter of its group of 8; the wave that arrives
+// last builds the mask words, moves the entries to their ranks, writes the ranks as the FP8 blocks' plane-S
+// bytes and puts the counter back to zero.  Nothing waits for anything.
+template <int kStWaves, int MT, int kXR, int kSrc, bool kPack = false>
 __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a)
 {
     constexpr int kStThreads = 64 * kStWaves;
@@ -594,6 +613,105 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
     int con_run = 0, con_c = 0;   // tile being multiplied
     int runs_closed = 0;
 
+    // v[mt][r] = the final sum of Y[m = 16 mt + 4 g + r][n = 16 grp + nl] before the tensor scales
+    auto emit = [&](const float4_t (&v)[MT], int grp) {
+        if constexpr (!kPack) {
+            const int64_t n = (int64_t)grp * 16 + nl;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = mt * 16 + 4 * g + r;
+                    if (m < M && n < N) Y[m * ldy + n] = v[mt][r] * ss;
+                }
+        } else {
+            // lane m takes the 16 results of output row m: through this wave's own slice of the reduction
+            // buffer (nobody else reads it here; LDS serves one wave's accesses in order)
+            float *tb = reinterpret_cast<float *>(&red[wave][0][0]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tb[(mt * 16 + 4 * g + r) * 16 + nl] = v[mt][r] * ss;
+            const int m = lane;
+            const bool valid = m < M, in_tile = m < ((M + kTileRows - 1) & ~(kTileRows - 1));
+            float x[16], f[16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float4_t t4 = *reinterpret_cast<const float4_t *>(&tb[(m & (16 * MT - 1)) * 16 + 4 * i]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[4 * i + e] = valid ? t4[e] : 0.0f;
+            }
+            // (the group's 16 sensitivities are the same for every lane: scalar loads, which the counted
+            // vector-memory waits of the stream do not see)
+            typedef const float __attribute__((address_space(4))) *const_floats_t;
+            const_floats_t fy = (const_floats_t)(a.fisher_y + (size_t)grp * kBlock);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) f[i] = valid ? fy[i] : 0.0f;
+            const float inv_Sy = 1.0f / a.S_y, S6y = 6.0f * a.S_y;
+            BlockCodes bc;
+            quantize_block_math<true, false>(x, f, block_amax(x), a.S_y, inv_Sy, S6y, -1, false, bc);
+            const bool hi = valid && bc.score > a.T_y;
+            const uint32_t decisions = (uint32_t)__ballot(hi);
+            const int y_nb = N / kBlock;
+            if (a.scores_y != nullptr && valid) a.scores_y[(int64_t)m * y_nb + grp] = bc.score;
+            const int unit = grp >> 3;
+            const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(a.y_packed, 0, (int)a.y_bytes, kStRsrc);
+            const __amdgpu_buffer_rsrc_t dbuf = __builtin_amdgcn_make_buffer_rsrc(a.dec, 0, a.n_groups * 4, kStRsrc);
+            if (in_tile) {
+                const uint32_t at = ((uint32_t)(m >> 3) * (uint32_t)a.y_n_kt + (uint32_t)unit) * kTileSlots + (uint32_t)(m & 7) * kTileBlocks + (uint32_t)(grp & 7);
+                u32x2_t lword = u32x2_t{bc.q[0], bc.q[1]};
+                if (hi) {
+                    float rr[16];
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) rr[e] = x[e] * inv_Sy;
+                    uint32_t c[4];
+                    encode_fp8_block<true, true>(rr, c);
+                    lword = u32x2_t{c[0], c[1]};
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{c[2], c[3]}, ybuf, (int)(a.y_off_H + at * 8u), 0, kCoherent);
+                } else {
+                    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)bc.sc, ybuf, (int)(a.y_off_S + at), 0, 0);
+                }
+                __builtin_amdgcn_raw_buffer_store_b64(lword, ybuf, (int)(a.y_off_L + at * 8u), 0, 0);
+            }
+            if (lane == 0) __builtin_amdgcn_raw_buffer_store_b32(decisions, dbuf, grp * 4, 0, kCoherent);
+            __builtin_amdgcn_s_waitcnt(0);
+            uint32_t before = 0;
+            if (lane == 0) before = __hip_atomic_fetch_add(&a.uctr[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            before = (uint32_t)__builtin_amdgcn_readfirstlane((int)before);
+            const int expected = a.n_groups - 8 * unit < 8 ? a.n_groups - 8 * unit : 8;
+            if (before == (uint32_t)(expected - 1)) {
+                // all row groups of this K-tile of the result have left their decisions and entries: lane = slot
+                const int gq = 8 * unit + (lane & 7);
+                const uint32_t d = __builtin_amdgcn_raw_buffer_load_b32(dbuf, gq < a.n_groups ? gq * 4 : (int)kStOutside, 0, kCoherent);
+                for (int rt = 0; rt * kTileRows < M; ++rt) {
+                    const bool fp8 = (d >> (rt * kTileRows + (lane >> 3))) & 1u;
+                    const uint64_t mask = __ballot(fp8);
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    const uint32_t tile = (uint32_t)rt * (uint32_t)a.y_n_kt + (uint32_t)unit, at = tile * kTileSlots + lane;
+                    // (every entry is in a register before the first one is stored: a store waits for its
+                    // data, i.e. for the load instruction as a whole.  Asking for all 64 entries together with
+                    // the decisions -- one round trip instead of two -- measured slower, 16.4 against 15.3 us.)
+                    const u32x2_t e = __builtin_amdgcn_raw_buffer_load_b64(ybuf, fp8 ? (int)(a.y_off_H + at * 8u) : (int)kStOutside, 0, kCoherent);
+                    if (fp8) {
+                        __builtin_amdgcn_raw_buffer_store_b64(e, ybuf, (int)(a.y_off_H + (tile * kTileSlots + rank) * 8u), 0, kCoherent);
+                        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)rank, ybuf, (int)(a.y_off_S + at), 0, 0);
+                    }
+                    if (gq >= a.n_groups) {   // K-blocks of the tile beyond N: FP4 zeros
+                        __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{0u, 0u}, ybuf, (int)(a.y_off_L + at * 8u), 0, 0);
+                        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)0, ybuf, (int)(a.y_off_S + at), 0, 0);
+                    }
+                    if (lane == 0) {
+                        __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{(uint32_t)mask, (uint32_t)(mask >> 32)}, ybuf, (int)(a.y_off_M + tile * 8u), 0, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(tile * kTileSlots, ybuf, (int)(a.y_off_T + tile * 4u), 0, 0);
+                    }
+                }
+                if (lane == 0) {
+                    __hip_atomic_store(&a.uctr[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (unit == 0) write_header(static_cast<PackedHeader *>(a.y_packed), make_layout(M, N), a.S_y, 0u);
+                }
+            }
+        }
+    };
     // acc[mt][r] = Y[m = 16 mt + 4 g + r][n = 16 grp + nl] (partial over this wave's K-tiles)
     auto close_run = [&](int grp) {
 #pragma unroll
@@ -613,16 +731,8 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
             __builtin_amdgcn_s_barrier();
         }
         if (kpi == 0) {
-            const int64_t n = (int64_t)grp * 16 + nl;
-            if (a.P_g == 1) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = mt * 16 + 4 * g + r;
-                        if (m < M && n < N) Y[m * ldy + n] = acc[mt][r] * ss;
-                    }
-            } else {
+            bool final_sums = a.P_g == 1;
+            if (!final_sums) {
                 // K is also split across workgroups: this part goes to memory (accesses that are
                 // coherent across the chip); whoever arrives last at the group's counter adds the parts
                 // in K order -- the result does not depend on who that is -- and clears the counter
@@ -643,15 +753,12 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
                         for (int mt = 0; mt < MT; ++mt) sum[mt] += load_coherent16(pbuf, base + (uint32_t)p * (MT * 1024u) + mt * 1024u);
                     }
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int m = mt * 16 + 4 * g + r;
-                            if (m < M && n < N) Y[m * ldy + n] = sum[mt][r] * ss;
-                        }
+                    for (int mt = 0; mt < MT; ++mt) acc[mt] = sum[mt];
+                    final_sums = true;
                     if (lane == 0) __hip_atomic_store(&a.gctr[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
+            if (final_sums) emit(acc, grp);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[mt] = acc2[mt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
@@ -803,23 +910,46 @@ size_t gemm_stream_scratch_bytes(int64_t M, int64_t N, int64_t K)
 #endif
 }
 
-template <int kSrc> static void launch_stream(const StreamPlan &p, const StreamArgs &a, hipStream_t st)
+template <int kSrc, bool kPack = false> static void launch_stream(const StreamPlan &p, const StreamArgs &a, hipStream_t st)
 {
     const dim3 grid((unsigned)p.grid), block((unsigned)(64 * p.waves));
-    if (p.xr == 1) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 1, kSrc>), grid, block, 0, st, a);
-    else if (p.mt == 1 && p.xr == 8) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 8, kSrc>), grid, block, 0, st, a);
-    else if (p.mt == 1) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 16, kSrc>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((gemm_stream_kernel<12, 2, 32, kSrc>), grid, block, 0, st, a);
+    if (p.xr == 1) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 1, kSrc, kPack>), grid, block, 0, st, a);
+    else if (p.mt == 1 && p.xr == 8) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 8, kSrc, kPack>), grid, block, 0, st, a);
+    else if (p.mt == 1) hipLaunchKernelGGL((gemm_stream_kernel<12, 1, 16, kSrc, kPack>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((gemm_stream_kernel<12, 2, 32, kSrc, kPack>), grid, block, 0, st, a);
+}
+
+// Whether the one-launch step can also quantize and pack its results (`po` without a gate): the counters of
+// both meetings -- parts of K per row group, row groups per K-tile of the result -- share the control region.
+constexpr int kStUnitCtr0 = 14336;   // first word of the second kind
+bool gemm_stream_packs(int64_t M, int64_t N, int64_t K)
+{
+    const StreamPlan p = stream_plan(M, N, K);
+    return kUseHwCvt && p.ok && N % kBlock == 0 && p.n_groups <= kStUnitCtr0 &&
+           (size_t)(kStUnitCtr0 + (p.n_groups + 7) / 8) * 4 <= kWsCtrlRegion;
+}
+// (Whether it pays: a row group's epilogue ends in a chain of memory round trips -- its stores acknowledged, the
+// counter, for the last of eight the others' decisions and entries -- while the other workgroups still stream at
+// full rate: 4-5 us that nothing overlaps with, against ~3 us for launching the standalone quantizer on staged
+// FP32 results.  Llama-2-7B linears, one launch / two launches inside a HIP graph, us: QKV 15.5 / 14.0 at M = 1,
+// 17.7 / 16.3 at M = 8, 22.6 / 20.3 at M = 32; FC1 20.6 / 19.5, 23.0 / 21.7, 36.9 / 29.3 -- where waves close
+// several row groups or parts of K meet first, every epilogue also drains the wave's loads in flight.  So the
+// library stages by default and quantizes in the launch on request.)
+// scratch of such a call: the partial sums, then one word of decisions per row group
+size_t gemm_stream_pack_scratch_bytes(int64_t M, int64_t N, int64_t K)
+{
+    return gemm_stream_scratch_bytes(M, N, K) + (size_t)align_up((uint64_t)((N + 15) / 16) * 4, 256);
 }
 
 // src: 0 bf16 X, 1 fp32 X (quantized in the kernel with fisher / T / S), 2 packed X.
 // ctrl: the workspace's control region (kWsCtrlRegion bytes, zero between calls); scratch: gemm_stream_scratch_bytes.
 fgmp_status_t gemm_stream(int src, const void *X, int64_t ldx, const float *fisher, float T, float S, const void *packed_X,
                           int64_t M, const void *packed_W, int64_t N, int64_t K, float *Y, int64_t ldy, void *ctrl,
-                          void *scratch, hipStream_t st)
+                          void *scratch, hipStream_t st, const PackOut *po)
 {
     const StreamPlan p = stream_plan(M, N, K);
     if (!p.ok || !kUseHwCvt) return FGMP_ERR_UNSUPPORTED;
+    if (po != nullptr && (po->gate || src == 2 || !gemm_stream_packs(M, N, K))) return FGMP_ERR_UNSUPPORTED;
     const PackedLayout lw = make_layout(N, K);
     StreamArgs a{};
     a.X = X; a.ldx = ldx; a.fisher = fisher; a.T = T; a.S = S;
@@ -833,6 +963,16 @@ fgmp_status_t gemm_stream(int src, const void *X, int64_t ldx, const float *fish
     a.n_tiles = (uint32_t)lw.n_tiles; a.n_rt = (uint32_t)lw.n_rt; a.n_kt = (int)lw.n_kt;
     a.w_rows = N; a.w_K = K;
     a.Y = Y; a.ldy = ldy; a.M = (int)M; a.N = (int)N; a.nb_x = (int)(K / kBlock);
+    if (po != nullptr) {
+        a.y_packed = po->out.hdr;
+        a.y_bytes = (uint32_t)po->layout.total_bytes;
+        a.y_off_L = (uint32_t)po->layout.off_L; a.y_off_S = (uint32_t)po->layout.off_S; a.y_off_M = (uint32_t)po->layout.off_M;
+        a.y_off_T = (uint32_t)po->layout.off_T; a.y_off_H = (uint32_t)po->layout.off_H;
+        a.y_n_kt = (int)po->layout.n_kt;
+        a.fisher_y = po->fisher; a.T_y = po->T; a.S_y = po->S; a.scores_y = po->scores;
+        a.dec = reinterpret_cast<uint32_t *>(static_cast<char *>(scratch) + p.total);
+        a.uctr = static_cast<uint32_t *>(ctrl) + kStUnitCtr0;
+    }
     a.gctr = static_cast<uint32_t *>(ctrl);
     a.partial = static_cast<float *>(scratch);
     a.partial_bytes = p.partial_bytes;
@@ -846,7 +986,10 @@ fgmp_status_t gemm_stream(int src, const void *X, int64_t ldx, const float *fish
 #ifdef FGMP_STREAM_TIMING
     a.dbg = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + p.total);
 #endif
-    if (src == 0) launch_stream<0>(p, a, st);
+    if (po != nullptr) {
+        if (src == 0) launch_stream<0, true>(p, a, st);
+        else launch_stream<1, true>(p, a, st);
+    } else if (src == 0) launch_stream<0>(p, a, st);
     else if (src == 1) launch_stream<1>(p, a, st);
     else launch_stream<2>(p, a, st);
     return hipGetLastError() == hipSuccess ? FGMP_OK : FGMP_ERR_HIP;

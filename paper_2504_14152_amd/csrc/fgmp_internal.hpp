@@ -70,7 +70,9 @@ bool gemm_stream_applies(int64_t M, int64_t N, int64_t K);
 size_t gemm_stream_scratch_bytes(int64_t M, int64_t N, int64_t K);
 fgmp_status_t gemm_stream(int src, const void *X, int64_t ldx, const float *fisher, float T, float S, const void *packed_X,
                           int64_t M, const void *packed_W, int64_t N, int64_t K, float *Y, int64_t ldy, void *ctrl,
-                          void *scratch, hipStream_t st);
+                          void *scratch, hipStream_t st, const PackOut *po = nullptr);
+bool gemm_stream_packs(int64_t M, int64_t N, int64_t K);
+size_t gemm_stream_pack_scratch_bytes(int64_t M, int64_t N, int64_t K);
 // packed -> zero-padded dense FP16 [8 n_rt_pad][ld]; one launch decodes one or two tensors and
 // can clear `zero_n` 32-bit counters
 struct DecodeJob {
@@ -90,6 +92,7 @@ struct PackOut {
     float T, S;            // threshold and tensor scale of the output tensor
     float *scores;         // nullable, M * N / 16
     int gate;              // nonzero: quantize SiLU(gate) * up of the 32 + 32 row groups of W; `out` is M x N / 2
+    int one_launch;        // nonzero: a decode step quantizes inside its launch (the default stages FP32 results: measured faster)
 };
 // The last, partly filled round of tiles of the prefill kernel, split along K (n_split 0: no split).
 struct SplitTail {

@@ -190,6 +190,12 @@ def workspace_bytes(M: int, N: int, K: int) -> int:
     return int(lib().fgmp_workspace_bytes(M, N, K))
 
 
+def workspace_bytes_packed_out(M: int, N: int, K: int, epilogue: int | None = None) -> int:
+    if epilogue is None:
+        return int(lib().fgmp_workspace_bytes_packed_out(M, N, K))
+    return int(lib().fgmp_workspace_bytes_packed_out_ex(M, N, K, int(epilogue)))
+
+
 WORKSPACE_CONTROL_BYTES = 65536   # FGMP_WORKSPACE_CONTROL_BYTES
 
 
@@ -209,7 +215,7 @@ def _alloc_packed(rows: int, K: int, device) -> Packed:
 
 
 SCORE_MODES = {"nvfp4_error": 0, "delta": 1}   # fgmp_score_mode_t
-EPILOGUE_NONE, EPILOGUE_SILU_GATE = 0, 1          # fgmp_epilogue_t
+EPILOGUE_NONE, EPILOGUE_SILU_GATE, EPILOGUE_ONE_LAUNCH = 0, 1, 0x100   # fgmp_epilogue_t (the last one is a flag)
 
 
 def quantize_weights(W: torch.Tensor, fisher: torch.Tensor, threshold: float, tensor_scale: float,
@@ -331,7 +337,7 @@ def quant_gemm_fused_packed_out(X: torch.Tensor, fisher_k: torch.Tensor, thresho
     if K != pW.K:
         raise FgmpError("K mismatch")
     N = pW.rows
-    n_out = N // 2 if epilogue == EPILOGUE_SILU_GATE else N
+    n_out = N // 2 if epilogue is not None and (epilogue & 0xFF) == EPILOGUE_SILU_GATE else N
     out = out or _alloc_packed(M, n_out, X.device)
     scores = torch.empty((M, n_out // 16), dtype=torch.float32, device=X.device) if want_scores else None
     if epilogue is None:

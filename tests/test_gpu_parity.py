@@ -662,6 +662,133 @@ def test_packed_output_epilogues_match_oracle_at_full_k():
     _assert_quant_equal(pH, scores, want, "gated packed output at full K")
 
 
+@pytest.mark.parametrize("M,K,N", [(1, 1024, 512), (8, 4096, 1536), (24, 2048, 528), (32, 4096, 2048), (8, 11008, 256),
+                                   (3, 512, 22016), (16, 256, 32)])
+def test_decode_step_quantizes_its_own_results_matches_oracle(M, K, N):
+    """The one-launch decode step (M <= 32) with quantized, packed results against the ORACLE: codes, block
+    scales, decisions and scores of the oracle's quantization of the oracle's product, on operands whose
+    product has no rounding in any summation order.  One and several runs per wave, 16 and 32 activation
+    rows, K in four and in two parts across workgroups (two chained meetings), a last K-tile of the result
+    with one row group (N % 128 = 16) and a result narrower than one K-tile, rows beyond M in the last
+    row-tile."""
+    _say(f"decode step, packed output vs oracle M={M} K={K} N={N}")
+    x = synth.exact_sum_operand_long_k(M, K, 83, 1)
+    w = synth.exact_sum_operand_long_k(N, K, 83, 2)
+    ones = np.ones(K, dtype=np.float32)
+    qx, qw = orc.quantize(x, ones, 0.0, 1.0), orc.quantize(w, ones, 0.0, 1.0)
+    ax, aw = orc.dequantize(qx["codes"], qx["scales"], qx["mask"]), orc.dequantize(qw["codes"], qw["scales"], qw["mask"])
+    assert np.array_equal(ax, x.astype(np.float64)) and np.array_equal(aw, w.astype(np.float64))
+    y64, _ = orc.gemm(ax, 1.0, aw, 1.0)
+    y32 = y64.astype(np.float32)
+    assert np.array_equal(y32.astype(np.float64), y64) and np.abs(y64).max() * 64 < 2 ** 24 / 16
+    f_n = synth.fisher_per_channel(N, 83, 3)
+    s_y = float(np.float32(np.abs(y32).max()) / np.float32(448.0))
+    T_y = orc.threshold(orc.quantize(y32, f_n, np.inf, s_y)["scores"], 0.25)
+    want = orc.quantize(y32, f_n, T_y, s_y)
+    assert 0 < want["mask"].sum() < want["mask"].size
+    xd, wd, od = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV), torch.from_numpy(ones).to(DEV)
+    pW = fgmp.quantize_weights(wd, od, 0.0, 1.0)
+    ws = fgmp.new_workspace(fgmp.workspace_bytes_packed_out(M, N, K), DEV)
+    base = fgmp.workspace_bytes(M, N, K)
+    ws[fgmp.WORKSPACE_CONTROL_BYTES:].fill_(0x5A)
+    pY, scores = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_n).to(DEV), T_y, s_y,
+                                                  want_scores=True, workspace=ws, epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    _assert_quant_equal(pY, scores, want, "decode step, packed output")
+    info = fgmp.packed_info(pY)
+    assert info["rows"] == M and info["K"] == N and info["n_fp8_blocks"] == int(want["mask"].sum())
+    assert abs(info["tensor_scale"] - s_y) <= 1e-7 * s_y
+    assert not bool(ws[:fgmp.WORKSPACE_CONTROL_BYTES].any()), "both kinds of counters are back at zero"
+    # one launch: no FP32 results were staged (the row groups' decision words sit right behind the call's own scratch)
+    staged_from = (base + 255) // 256 * 256 + (N // 4 + 255) // 256 * 256
+    assert bool((ws[staged_from:] == 0x5A).all()), "the results were staged in the workspace"
+    # a second call on the same workspace; the library's own choice between one launch and two (same tensor
+    # either way); the next layer on the packed result
+    pY2 = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_n).to(DEV), T_y, s_y, workspace=ws,
+                                           epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(pY), fgmp.unpack_canonical(pY2)))
+    pY3, sc3 = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_n).to(DEV), T_y, s_y, want_scores=True)
+    _assert_quant_equal(pY3, sc3, want, "decode step, packed output, default path")
+    w2 = synth.weights(64, N, 83, 4)
+    w2d, w2ref = _to_dev_bf16(w2)
+    f2 = synth.fisher_per_channel(N, 83, 5)
+    s2 = float(synth.default_tensor_scale(w2ref))
+    pW2 = fgmp.quantize_weights(w2d, torch.from_numpy(f2).to(DEV), np.inf, s2)
+    Z = fgmp.gemm(pY, pW2)
+    q2 = orc.quantize(w2ref, f2, np.inf, s2)
+    zw, tol = orc.gemm(orc.dequantize(want["codes"], want["scales"], want["mask"]), s_y,
+                       orc.dequantize(q2["codes"], q2["scales"], q2["mask"]), s2)
+    assert np.all(np.abs(Z.cpu().numpy().astype(np.float64) - zw) <= tol)
+
+
+@pytest.mark.parametrize("M,K,N,dtype", [(1, 4096, 12288, "bf16"), (8, 4096, 22016, "bf16"), (32, 4096, 12288, "fp32"),
+                                          (8, 11008, 4096, "bf16"), (19, 1152, 528, "fp32")])
+def test_decode_step_packed_output_on_random_inputs_is_consistent(M, K, N, dtype):
+    """On ordinary inputs, at the Llama-2-7B decode shapes: the packed results of the one-launch step equal the
+    standalone quantizer run on the very FP32 results the plain step writes (same arithmetic on the same
+    values), scores included -- and the build whose waits are all full ones gives the same tensor."""
+    from paper_2504_14152_amd import build
+    _say(f"decode step, packed output vs standalone quantizer {M}x{K}x{N} {dtype}")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(230 + N)
+    wd = torch.empty((N, K), dtype=torch.bfloat16, device=DEV).normal_(0.0, 0.02, generator=gen)
+    x = synth.activations(M, K, 93, 1)
+    xd, xref = (torch.from_numpy(x).to(DEV), x) if dtype == "fp32" else _to_dev_bf16(x)
+    fxd = torch.from_numpy(synth.fisher_per_channel(K, 93, 3)).to(DEV)
+    sx, sw = float(synth.default_tensor_scale(xref)), float(wd.abs().max().float()) / 448.0
+    _, sws = fgmp.quantize_weights(wd, fxd, np.inf, sw, want_scores=True)
+    pW = fgmp.quantize_weights(wd, fxd, fgmp.threshold_for_fraction(sws, 0.1), sw)
+    del sws, wd
+    Tx = fgmp.threshold_for_fraction(fgmp.quantize_activations(xd, fxd, np.inf, sx, want_scores=True)[1], 0.1)
+    Y = fgmp.quant_gemm_fused(xd, fxd, Tx, sx, pW)
+    f_n = torch.from_numpy(synth.fisher_per_channel(N, 93, 9)).to(DEV)
+    s_y = float(Y.abs().max()) / 448.0
+    _, sc0 = fgmp.quantize_activations(Y, f_n, np.inf, s_y, want_scores=True)
+    T_y = fgmp.threshold_for_fraction(sc0, 0.2)
+    ref, sc_ref = fgmp.quantize_activations(Y, f_n, T_y, s_y, want_scores=True)
+    got, sc_got = fgmp.quant_gemm_fused_packed_out(xd, fxd, Tx, sx, pW, f_n, T_y, s_y, want_scores=True,
+                                                   epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    assert torch.equal(sc_ref, sc_got)
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(ref), fgmp.unpack_canonical(got)))
+    assert fgmp.packed_info(got)["n_fp8_blocks"] == fgmp.packed_info(ref)["n_fp8_blocks"] > 0
+    with fgmp.use_library(build.lib_path("fullwait")):
+        full = fgmp.quant_gemm_fused_packed_out(xd, fxd, Tx, sx, pW, f_n, T_y, s_y, epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(full), fgmp.unpack_canonical(got)))
+
+
+@pytest.mark.parametrize("M,K,N", [(272, 128, 512), (32, 2048, 1024)])
+def test_packed_results_are_valid_weight_operands(M, K, N):
+    """A reader may take a block's plane-H entry from the mask alone (the number of FP8 slots before the block in
+    its tile), as the decode kernel does for its weight operand.  So the tensors the quantizing epilogues write
+    -- prefill kernel and one-launch decode step -- must serve as W of a decode step like any other packed
+    tensor: products against the oracle's, with the oracle's quantization of the exact results as the operand."""
+    _say(f"packed results as weight operand M={M} K={K} N={N}")
+    x = synth.exact_sum_operand_long_k(M, K, 87, 1)
+    w = synth.exact_sum_operand_long_k(N, K, 87, 2)
+    ones = np.ones(K, dtype=np.float32)
+    y64, _ = orc.gemm(x.astype(np.float64), 1.0, w.astype(np.float64), 1.0)
+    y32 = y64.astype(np.float32)
+    assert np.array_equal(y32.astype(np.float64), y64)
+    f_n = synth.fisher_per_channel(N, 87, 3)
+    s_y = float(np.float32(np.abs(y32).max()) / np.float32(448.0))
+    T_y = orc.threshold(orc.quantize(y32, f_n, np.inf, s_y)["scores"], 0.3)
+    want = orc.quantize(y32, f_n, T_y, s_y)
+    xd, wd, od = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV), torch.from_numpy(ones).to(DEV)
+    pW = fgmp.quantize_weights(wd, od, 0.0, 1.0)
+    pY = fgmp.quant_gemm_fused_packed_out(xd, od, 0.0, 1.0, pW, torch.from_numpy(f_n).to(DEV), T_y, s_y,
+                                          epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    _assert_quant_equal(pY, None, want, "packed result")
+    # 5 new activation rows times the packed result as an M x N weight tensor
+    v = synth.activations(5, N, 87, 6)
+    vd, vref = _to_dev_bf16(v)
+    f_v = synth.fisher_per_channel(N, 87, 7)
+    s_v = float(synth.default_tensor_scale(vref))
+    qv = orc.quantize(vref, f_v, np.inf, s_v)
+    Z = fgmp.quant_gemm_fused(vd, torch.from_numpy(f_v).to(DEV), np.inf, s_v, pY)
+    zw, tol = orc.gemm(orc.dequantize(qv["codes"], qv["scales"], qv["mask"]), s_v,
+                       orc.dequantize(want["codes"], want["scales"], want["mask"]), s_y)
+    assert np.all(np.abs(Z.cpu().numpy().astype(np.float64) - zw) <= tol)
+
+
 @pytest.mark.parametrize("M,K,N", [(200, 512, 320), (4352, 256, 4096), (9, 1024, 192)])
 def test_gated_packed_output_on_random_inputs_is_consistent(M, K, N):
     """On ordinary inputs: the gated epilogue equals the oracle's gate applied to the very FP32 results
