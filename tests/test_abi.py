@@ -59,6 +59,11 @@ def test_sizes_and_host_side_argument_checks():
     assert wb(64, 96, 128, 1) == 0 and wb(64, 128, 128, 7) == 0
     assert wb(64, 128, 128, 0) == fgmp.lib().fgmp_workspace_bytes_packed_out(64, 128, 128)
     assert wb(64, 128, 128, 1) >= wb(64, 128, 128, 0) + 64 * 64 * 4
+    # the one-launch flag changes no size and is no operator of its own
+    assert wb(8, 12288, 4096, 0x100) == wb(8, 12288, 4096, 0) and wb(64, 128, 128, 0x101) == wb(64, 128, 128, 1)
+    assert wb(64, 128, 128, 0x102) == 0 and wb(64, 128, 128, 0x200) == 0
+    # ... and a decode step's workspace has room for its row groups' decision words behind its own scratch
+    assert wb(8, 12288, 4096, 0x100) >= fgmp.workspace_bytes(8, 12288, 4096) + 12288 // 16 * 4
     assert L.fgmp_quant_gemm_fused_packed_out_ex(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 96, 1, 256, 0.0, 1.0, 256, 1 << 20,
                                                  None, 256, 1 << 30, None) == -2
     assert L.fgmp_quant_gemm_fused_packed_out_ex(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 128, 5, 256, 0.0, 1.0, 256, 1 << 20,
