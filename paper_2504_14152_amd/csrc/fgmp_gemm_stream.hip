@@ -766,7 +766,7 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
     };
     // one K-tile: decode (b[4 j + i] = halves 2i, 2i+1 of MFMA j's B operand; MFMA j reduces over the K
     // elements 32 g + 8 j .. + 7 of the tile), multiply, and close the run after its last tile
-    auto consume = [&](const StreamSlot &s) {
+    auto consume = [&](StreamSlot &s) {
         half2_t b[16];
         const uint32_t bits = ((upper ? s.m[1] : s.m[0]) >> sh) & 3u;
         // (both blocks FP8: their entries are neighbours; one: its entry came first)
@@ -775,6 +775,8 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
         st_decode_block(make_uint2(s.l[2], s.l[3]), s.s >> 8, bits & 2u, make_uint2(both ? s.up[2] : s.up[0], both ? s.up[3] : s.up[1]),
                         reinterpret_cast<half2_t(&)[8]>(b[8]));
         const half8_t *bv = reinterpret_cast<const half8_t *>(b);
+        // the slot's registers are free from here on: its next tile is requested before the products, not after
+        issue_tile(s);
         const _Float16 *xc = xrow_p + (kt_b - kt_part0 + con_c) * kTileK;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -800,7 +802,6 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
         st_wait_all<st_step_wait(T)>(ring[J]);                                        \
         if constexpr ((T) >= kStFirstH) issue_h(ring[((J) + kStHLead) % kStRing]);     \
         consume(ring[J]);                                                             \
-        issue_tile(ring[J]);                                                          \
     }
         ST_STEP(0, 0) ST_STEP(1, 1) ST_STEP(2, 2) ST_STEP(3, 3)
         ST_STAMP(4);
@@ -811,7 +812,6 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
         st_wait_all<st_step_wait(kStRing + (J))>(ring[J]);                 \
         issue_h(ring[((J) + kStHLead) % kStRing]);                         \
         consume(ring[J]);                                                  \
-        issue_tile(ring[J]);                                               \
     }
             ST_LOOP_STEP(0) ST_LOOP_STEP(1) ST_LOOP_STEP(2) ST_LOOP_STEP(3)
 #undef ST_LOOP_STEP
