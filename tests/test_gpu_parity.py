@@ -1290,3 +1290,40 @@ def test_fused_call_replays_in_a_hip_graph(M, K, N):
         Z = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
         assert torch.equal(Z, Y_eager)
 
+
+@pytest.mark.parametrize("M,K,N", [(8, 1024, 512), (24, 2048, 528)])
+def test_decode_step_with_packed_output_replays_in_a_hip_graph(M, K, N):
+    """The one-launch step that quantizes its own results, captured and replayed: both kinds of arrival
+    counters (parts of K per row group, row groups per tile of the result) are back at zero after every
+    replay, whatever the scratch holds in between, and every replay writes the eager call's tensor."""
+    c = _quantized_pair(M, K, N, 47, 0.1, per_elem_w=False)
+    f_n = torch.from_numpy(synth.fisher_per_channel(N, 47, 9)).to(DEV)
+    Y = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+    s_y = float(Y.abs().max()) / 448.0
+    T_y = fgmp.threshold_for_fraction(fgmp.quantize_activations(Y, f_n, np.inf, s_y, want_scores=True)[1], 0.2)
+    ws = fgmp.new_workspace(fgmp.workspace_bytes_packed_out(M, N, K), DEV)
+    args = (c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], f_n, T_y, s_y)
+    want = [t.clone() for t in fgmp.unpack_canonical(fgmp.quant_gemm_fused_packed_out(*args, epilogue=fgmp.EPILOGUE_ONE_LAUNCH))]
+    assert int(want[2].sum()) > 0
+    pY = fgmp.quant_gemm_fused_packed_out(*args, workspace=ws, epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fgmp.quant_gemm_fused_packed_out(*args, out=pY, workspace=ws, epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fgmp.quant_gemm_fused_packed_out(*args, out=pY, workspace=ws, epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+    for rep in range(4):
+        pY.buf.fill_(0x3C)
+        ws[fgmp.WORKSPACE_CONTROL_BYTES:].fill_(0xA5 if rep & 1 else 0)
+        assert not bool(ws[:fgmp.WORKSPACE_CONTROL_BYTES].any()), "every call leaves the control region zero"
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = fgmp.unpack_canonical(pY)
+        assert all(torch.equal(u, v) for u, v in zip(got, want)), f"replay {rep}"
+        Z = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])   # eager work between replays
+        assert torch.equal(Z, Y)
+
