@@ -321,6 +321,13 @@ def main() -> int:
                                          "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
                                          "frac_of_measured_copy": round(gbps / copy_gbps, 4),
                                          "algorithmic_bytes": int(qbytes)}
+        # what the memory system alone takes for the kernel's access pattern: the same kernel with its arithmetic
+        # taken out (measurement build), and the real kernel from the same build right after it
+        with fgmp.use_library(fgmp_build.lib_path("hooks")):
+            ms_traffic = timed(lambda: fgmp.selftest_quantizer_traffic(xqd, fq, pq), 20, 3)
+            ms_q_again = timed(lambda: fgmp.quantize_activations(xqd, fq, Tq, sq, out=pq), 20, 3)
+        extra["act_quant_16384x8192"].update({"ms_traffic_model": round(ms_traffic, 4), "ms_same_run": round(ms_q_again, 4),
+                                              "traffic_model_over_kernel": round(ms_traffic / ms_q_again, 4)})
         # the same pass with the Eq. 8 score (error increase of NVFP4 over FP8): threshold recalibrated for 10%
         _, sc = fgmp.quantize_activations(xqd, fq, float("inf"), sq, want_scores=True, score_mode="delta")
         Tqd = fgmp.threshold_for_fraction(sc, P_FP8)
@@ -443,6 +450,8 @@ def main() -> int:
         q = extra["act_quant_16384x8192"]
         roofline["quantizer"] = {"bound": "hbm", "kernel": "quantize_act_kernel", "achieved": q["GBps"], "peak": PEAK_HBM_GBPS,
                                  "unit": "GB/s", "frac": q["frac_hbm_peak"], "us_per_launch": round(q["ms"] * 1e3, 2),
+                                 "us_traffic_model": round(q["ms_traffic_model"] * 1e3, 2),
+                                 "frac_of_traffic_model": q["traffic_model_over_kernel"],
                                  "workload": "16384 x 8192 bf16 -> packed, 10% FP8 blocks"}
     def prefill_case(Mp_, Kp_, Np_, p_w, p_x, kind, tid):
         """Fused step on another prefill shape; returns ms and TFLOP/s (per-channel weight Fisher)."""

@@ -375,6 +375,20 @@ fgmp_status_t fgmp_selftest_mfma_rate(int64_t workgroups, int32_t iters, float *
  */
 fgmp_status_t fgmp_selftest_time_gemm_kernel(void *ev_start, void *ev_stop);
 
+/*
+ * Measurement reference for the activation quantizer (Sec. 4.2 as a memory-bound pass): the quantizer's
+ * kernel for large tensors with its arithmetic taken out -- the same loads of X, the same stores to the
+ * planes of `packed_out` (a fixed tenth of the blocks written as FP8), contents meaningless -- so that
+ * the benchmark can put the time the memory system alone takes for this access pattern beside the real
+ * kernel's, in the same run.  Arguments as fgmp_quantize_activations (bf16 or fp32 X, per-channel
+ * `fisher_k`, which is read but not used).  Only libraries built with FGMP_MEASUREMENT_HOOKS have it;
+ * elsewhere, and for tensors too small for that kernel (fewer than 65536 tiles of 8 x 128), it returns
+ * FGMP_ERR_UNSUPPORTED.
+ */
+fgmp_status_t fgmp_selftest_quantizer_traffic(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                              const float *fisher_k, void *packed_out, size_t packed_bytes,
+                                              void *stream);
+
 #ifdef __cplusplus
 }
 #endif

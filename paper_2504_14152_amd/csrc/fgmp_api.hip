@@ -286,4 +286,15 @@ fgmp_status_t fgmp_selftest_time_gemm_kernel(void *ev_start, void *ev_stop)
                : (ev_start == nullptr ? FGMP_OK : FGMP_ERR_UNSUPPORTED);   // clearing "nothing" always works
 }
 
+fgmp_status_t fgmp_selftest_quantizer_traffic(const void *X, fgmp_dtype_t dt, int64_t M, int64_t K, int64_t ldx,
+                                              const float *fisher_k, void *packed_out, size_t packed_bytes, void *stream)
+{
+#ifdef FGMP_MEASUREMENT_HOOKS
+    return quantize_traffic_model(X, dt, M, K, ldx, fisher_k, packed_out, packed_bytes, as_stream(stream));
+#else
+    (void)X; (void)dt; (void)M; (void)K; (void)ldx; (void)fisher_k; (void)packed_out; (void)packed_bytes; (void)stream;
+    return FGMP_ERR_UNSUPPORTED;
+#endif
+}
+
 }  // extern "C"

@@ -24,6 +24,10 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
                               _Float16 *x16 = nullptr, int64_t ld16 = 0, uint32_t *zero = nullptr,
                               int64_t zero_n = 0, int score_mode = FGMP_SCORE_NVFP4_ERROR,
                               uint8_t *clip_scales = nullptr);
+#ifdef FGMP_MEASUREMENT_HOOKS
+fgmp_status_t quantize_traffic_model(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx, const float *fisher,
+                                     void *packed, size_t packed_bytes, hipStream_t st);
+#endif
 fgmp_status_t unpack_tensor(const void *packed, int64_t rows, int64_t K, uint8_t *codes, uint8_t *scales,
                             uint8_t *mask, hipStream_t st);
 fgmp_status_t gemm_packed(const void *packed_X, int64_t M, const void *packed_W, int64_t N, int64_t K,

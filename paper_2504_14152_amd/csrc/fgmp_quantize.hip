@@ -277,10 +277,14 @@ constexpr int kQWaves = 8;    // waves per workgroup = consecutive K-tiles
 constexpr int kQBatch = 8;    // row-tiles between two writes of the gathered plane-M words
 constexpr int64_t kQMinTiles = 65536;   // smaller tensors do not fill the resident set for long enough: general kernel
 
-template <typename Tin, int kMode>
+// kTraffic (measurement builds only): the kernel's loads and stores with next to no arithmetic between them
+// -- the plane-L words are input words, a fixed tenth of the slots counts as FP8 -- i.e. what the memory
+// system alone takes for this access pattern; the benchmark times it beside the real kernel.
+template <typename Tin, int kMode, bool kTraffic = false>
 __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams p, uint32_t x_bytes, uint32_t out_bytes, int n_kg)
 {
     static_assert(kMode == kModeStrided || kMode == kModeF16, "one-pass modes only");
+    static_assert(!kTraffic || kMode == kModeStrided, "the traffic model writes packed planes");
     constexpr int kVec = (int)(sizeof(RawBlock<Tin>) / sizeof(uint4));   // 16-byte loads per block
     __shared__ float2 tbl[128];                                            // {d, 1/d} by scale code
     __shared__ uint4 m_lds[kQBatch][kQWaves];                              // plane-M word and plane-T entry, [row-tile of the batch][K-tile]
@@ -346,6 +350,27 @@ __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams 
 
     auto process = [&](int it, const RawBlock<Tin> &raw_in) {
         const int rt = rt_first + it * rt_step;
+        if constexpr (kTraffic) {
+            uint32_t w[4] = {raw_in.v[0].x ^ raw_in.v[1].z, raw_in.v[0].y ^ raw_in.v[1].w, raw_in.v[0].z ^ raw_in.v[1].x, raw_in.v[0].w ^ raw_in.v[1].y};
+            if constexpr (kVec == 4) {
+                w[0] ^= raw_in.v[2].x ^ raw_in.v[3].z; w[1] ^= raw_in.v[2].y ^ raw_in.v[3].w;
+                w[2] ^= raw_in.v[2].z ^ raw_in.v[3].x; w[3] ^= raw_in.v[2].w ^ raw_in.v[3].y;
+            }
+            const uint32_t row = (uint32_t)(rt * kTileRows + rloc);
+            const bool valid = kvalid && row < (uint32_t)p.rows;
+            const uint32_t tile = (uint32_t)rt * (uint32_t)p.n_kt + kt, slot = tile * kTileSlots + lane;
+            const bool hi = valid && ((slot * 2654435761u) >> 24) < 26u;
+            const uint64_t ballot = __ballot(hi);
+            const uint32_t prefix = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+            if (lane == 0) m_lds[it % kQBatch][wave] = make_uint4((uint32_t)ballot, (uint32_t)(ballot >> 32), h_cnt, 0u);
+            if (hi) __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{w[2], w[3]}, obuf, (int)(off_H + (h_cnt + prefix) * 8u), 0, 0);
+            if (kt < (uint32_t)p.n_kt) {
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{w[0], w[1]}, obuf, (int)(off_L + slot * 8u), 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(hi ? prefix : (w[2] & 0x7Fu)), obuf, (int)(off_S + slot), 0, 0);
+            }
+            h_cnt += (uint32_t)__popcll(ballot);
+            return;
+        }
         float x[16];
         widen(raw_in, x);
         const float amax = block_amax(x);
@@ -630,6 +655,21 @@ static void launch_quantize(const QuantParams &p, bool per_elem, dim3 grid, hipS
     }
 }
 
+#ifdef FGMP_MEASUREMENT_HOOKS
+// (measurement builds: the next activation tensor that takes the trimmed kernel runs its traffic model instead)
+static thread_local bool g_traffic_model = false;
+fgmp_status_t quantize_traffic_model(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx, const float *fisher,
+                                     void *packed, size_t packed_bytes, hipStream_t st)
+{
+    if (make_layout(rows, K).n_tiles < kQMinTiles) return FGMP_ERR_UNSUPPORTED;
+    g_traffic_model = true;
+    const fgmp_status_t rc = quantize_tensor(X, dt, rows, K, ldx, fisher, 0, 0.0f, 1.0f, packed, packed_bytes, nullptr, false, st);
+    const bool ran = !g_traffic_model;
+    g_traffic_model = false;
+    return rc != FGMP_OK ? rc : ran ? FGMP_OK : FGMP_ERR_UNSUPPORTED;
+}
+#endif
+
 fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int64_t K, int64_t ldx,
                               const float *fisher, int64_t ld_fisher, float T, float S, void *packed,
                               size_t packed_bytes, float *scores, bool compact, hipStream_t st,
@@ -702,10 +742,14 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
                       l.n_tiles >= kQMinTiles;
     if (fast) {
         p.mode = x16 != nullptr ? kModeF16 : kModeStrided;
-        // one resident set of workgroups (three of eight waves per compute unit), a multiple of the number of
-        // K groups, with the row-tiles dealt out evenly
+        // one resident set of workgroups, a multiple of the number of K groups, with the row-tiles dealt out
+        // evenly: two workgroups of eight waves per compute unit.  (The kernel's 85-93 registers let five waves
+        // share a SIMD, i.e. two such workgroups a compute unit: a grid of three per compute unit ran its last
+        // third as a second round, 72.9 us on 16384 x 8192 against 69.3; one per compute unit 81.6; three that
+        // do fit -- the sensitivities moved to LDS, 74 registers -- 74.3: more waves only crowd the memory system.)
+        constexpr int64_t kQResident = 512;
         const int64_t n_kg = (l.n_kt + kQWaves - 1) / kQWaves;
-        int64_t gy = std::max<int64_t>(1, (int64_t)768 / n_kg);
+        int64_t gy = std::max<int64_t>(1, kQResident / n_kg);
         if (gy > l.n_rt) gy = l.n_rt;
         const int64_t its = (l.n_rt + gy - 1) / gy;
         gy = (l.n_rt + its - 1) / its;
@@ -714,6 +758,12 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
         if (x16 != nullptr) {
             if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeF16>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
             else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeF16>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+#ifdef FGMP_MEASUREMENT_HOOKS
+        } else if (g_traffic_model) {
+            g_traffic_model = false;
+            if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeStrided, true>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+            else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeStrided, true>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+#endif
         } else {
             if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeStrided>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
             else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeStrided>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);

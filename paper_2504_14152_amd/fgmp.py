@@ -140,6 +140,8 @@ def _load(path: str) -> ctypes.CDLL:
     L.fgmp_selftest_mfma_rate.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp]
     L.fgmp_selftest_time_gemm_kernel.restype = ctypes.c_int
     L.fgmp_selftest_time_gemm_kernel.argtypes = [vp, vp]
+    L.fgmp_selftest_quantizer_traffic.restype = ctypes.c_int
+    L.fgmp_selftest_quantizer_traffic.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, sz, vp]
     return L
 
 
@@ -449,6 +451,14 @@ def selftest_time_gemm_kernel(start: "torch.cuda.Event | None", stop: "torch.cud
     if (start is not None and hs == 0) or (stop is not None and he == 0):
         raise FgmpError("timing events must be recorded once before they are handed to the library")
     _check(lib().fgmp_selftest_time_gemm_kernel(hs or None, he or None), "fgmp_selftest_time_gemm_kernel")
+
+
+def selftest_quantizer_traffic(X: torch.Tensor, fisher_k: torch.Tensor, out: Packed) -> None:
+    """Launch the traffic model of the activation quantizer (measurement builds only; the caller times it)."""
+    _require_cuda(X, fisher_k)
+    M, K = X.shape
+    _check(lib().fgmp_selftest_quantizer_traffic(_ptr(X), _dtype_code(X), M, K, X.stride(0), _ptr(fisher_k), _ptr(out.buf),
+                                                 out.buf.numel(), _stream()), "fgmp_selftest_quantizer_traffic")
 
 
 def selftest_decode_table(fmt: int, device="cuda"):

@@ -75,6 +75,8 @@ def test_sizes_and_host_side_argument_checks():
     assert L.fgmp_quant_gemm_fused_packed_out(256, 0, 64, 128, 128, 256, 0.0, 1.0, 256, 32, 256, 0.0, 1.0, 256, 16,
                                               None, 256, 1 << 20, None) == -4   # packed output buffer too small
     assert L.fgmp_threshold_for_fraction_multi(None, None, 1, ctypes.c_double(0.1), None, None) == -1
+    # the quantizer's traffic model exists in measurement builds only
+    assert L.fgmp_selftest_quantizer_traffic(256, 0, 16384, 8192, 8192, 256, 256, 1 << 30, None) == -5
 
 
 def test_bench_refuses_more_than_one_gpu():
