@@ -280,7 +280,8 @@ constexpr int64_t kQMinTiles = 65536;   // smaller tensors do not fill the resid
 // kTraffic (measurement builds only): the kernel's loads and stores with next to no arithmetic between them
 // -- the plane-L words are input words, a fixed tenth of the slots counts as FP8 -- i.e. what the memory
 // system alone takes for this access pattern; the benchmark times it beside the real kernel.
-template <typename Tin, int kMode, bool kTraffic = false>
+// kDelta: the score of Eq. 8 (the FP8 codes of every block are computed first and reused for the blocks kept in FP8).
+template <typename Tin, int kMode, bool kTraffic = false, bool kDelta = false>
 __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams p, uint32_t x_bytes, uint32_t out_bytes, int n_kg)
 {
     static_assert(kMode == kModeStrided || kMode == kModeF16, "one-pass modes only");
@@ -384,6 +385,16 @@ __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams 
         const uint32_t sc = e4m3_encode_pair_hw(u, 0.0f) & 0xFFu;
         const float2 dd = tbl[sc];
         const float d = dd.x, inv_d = dd.y;
+        // (Eq. 8: the FP8 codes of every block; values beyond the FP8 range only occur when the caller's S is
+        // below amax / 448, then the wave clamps before converting -- clamping changes no value in range)
+        uint32_t c8[4] = {0u, 0u, 0u, 0u};
+        if constexpr (kDelta) {
+            float r8[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) r8[i] = x[i] * inv_S;
+            if (__ballot(amax * inv_S > 448.0f) != 0ull) encode_fp8_block<true, true>(r8, c8);
+            else encode_fp8_block<true, false>(r8, c8);
+        }
         uint32_t q[2] = {0u, 0u};
         float t[16];
 #define FGMP_ENC(W, B, I) q[W] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q[W], x[I] * inv_d, x[I + 1] * inv_d, 1.0f, B)
@@ -393,7 +404,15 @@ __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams 
 #define FGMP_ERR(W, B, I)                                                                \
     {                                                                                    \
         const float2_t v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(q[W], 1.0f, B);      \
-        const float e0 = x[I] - v[0] * d, e1 = x[I + 1] - v[1] * d;                      \
+        float e0, e1;                                                                    \
+        if constexpr (kDelta) {                                                          \
+            const float2_t v8 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(c8[(I) / 4], 1.0f, ((I) % 4) >= 2); \
+            e0 = v[0] * d - v8[0] * S;                                                   \
+            e1 = v[1] * d - v8[1] * S;                                                   \
+        } else {                                                                         \
+            e0 = x[I] - v[0] * d;                                                        \
+            e1 = x[I + 1] - v[1] * d;                                                    \
+        }                                                                                \
         t[I] = (e0 * e0) * f[I];                                                         \
         t[I + 1] = (e1 * e1) * f[I + 1];                                                 \
     }
@@ -416,12 +435,17 @@ __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams 
         if constexpr (kMode == kModeF16) {
             half2_t o[8];
             if (hi) {
-                float r[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
                 uint32_t c[4];
-                if (amax * inv_S > 448.0f) encode_fp8_block<true, true>(r, c);
-                else encode_fp8_block<true, false>(r, c);
+                if constexpr (kDelta) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) c[j] = c8[j];
+                } else {
+                    float r[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                    if (amax * inv_S > 448.0f) encode_fp8_block<true, true>(r, c);
+                    else encode_fp8_block<true, false>(r, c);
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     o[2 * j] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(c[j], 1.0f, false);
@@ -456,12 +480,17 @@ __global__ __launch_bounds__(64 * kQWaves) void quantize_act_kernel(QuantParams 
                 // values beyond the FP8 range only occur when the caller's S is below amax / 448
                 const bool any_big = __ballot(hi && amax * inv_S > 448.0f) != 0ull;
                 if (hi) {
-                    float r[16];
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
                     uint32_t c[4];
-                    if (any_big) encode_fp8_block<true, true>(r, c);
-                    else encode_fp8_block<true, false>(r, c);
+                    if constexpr (kDelta) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) c[j] = c8[j];
+                    } else {
+                        float r[16];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) r[i] = x[i] * inv_S;
+                        if (any_big) encode_fp8_block<true, true>(r, c);
+                        else encode_fp8_block<true, false>(r, c);
+                    }
                     lw0 = c[0];
                     lw1 = c[1];
                     sbyte = prefix;
@@ -737,7 +766,7 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
     // scales) runs on the trimmed kernel when its 32-bit offsets and its shortcut division apply.
     const uint64_t x_bytes = (uint64_t)rows * (uint64_t)ldx * (uint64_t)esz;
     // (offsets: the input plus one stride of the resident set past its end must stay below 2^32)
-    const bool fast = kUseHwCvt && !compact && !per_elem && !p.delta && clip_scales == nullptr &&
+    const bool fast = kUseHwCvt && !compact && !per_elem && clip_scales == nullptr &&
                       x_bytes < 0x7FFFFF00ull && l.total_bytes < 0xFFFFFF00ull && S >= 1e-30f && S <= 1e30f &&
                       l.n_tiles >= kQMinTiles;
     if (fast) {
@@ -755,7 +784,16 @@ fgmp_status_t quantize_tensor(const void *X, fgmp_dtype_t dt, int64_t rows, int6
         gy = (l.n_rt + its - 1) / its;
         const dim3 fgrid((unsigned)(n_kg * gy));
         const uint32_t out_bytes = packed ? (uint32_t)(x16 != nullptr ? sizeof(PackedHeader) : l.total_bytes) : 0u;
-        if (x16 != nullptr) {
+        if (p.delta) {
+            // the Eq. 8 score
+            if (x16 != nullptr) {
+                if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeF16, false, true>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+                else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeF16, false, true>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+            } else {
+                if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeStrided, false, true>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+                else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeStrided, false, true>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
+            }
+        } else if (x16 != nullptr) {
             if (dt == FGMP_F32) hipLaunchKernelGGL((quantize_act_kernel<float, kModeF16>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
             else hipLaunchKernelGGL((quantize_act_kernel<uint16_t, kModeF16>), fgrid, dim3(64 * kQWaves), 0, st, p, (uint32_t)x_bytes, out_bytes, (int)n_kg);
 #ifdef FGMP_MEASUREMENT_HOOKS

@@ -168,6 +168,45 @@ def test_quantize_activations_standalone_size_sampled_rows():
     assert np.array_equal(scores[ridx].cpu().numpy().view(np.uint32), want["scores"].view(np.uint32))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_quantize_activations_delta_score_large_tensor_sampled_rows(dtype):
+    """The Eq. 8 score on a tensor large enough for the trimmed activation kernel (8192 x 8192: 65536 tiles),
+    with a tensor scale small enough that some values exceed the FP8 range (the clamping path): 96 whole rows
+    against the oracle -- codes, scales, decisions, scores -- and the whole tensor against the general kernel's
+    result on a row slice that it serves (same arithmetic)."""
+    rows_n, K, p = 8192, 8192, 0.1
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(26)
+    x = torch.empty((rows_n, K), dtype=torch.float32, device=DEV).normal_(0.0, 1.0, generator=gen)
+    ch = torch.randperm(K, device=DEV, generator=gen)[: K // 100]
+    x[:, ch] *= 20.0
+    xd = x.to(torch.bfloat16) if dtype == "bf16" else x
+    del x
+    f = synth.fisher_per_channel(K, 0, 26)
+    fd = torch.from_numpy(f).to(DEV)
+    S = float(xd.abs().max().float()) / 448.0 / 1.5
+    _, sc = fgmp.quantize_activations(xd, fd, np.inf, S, want_scores=True, score_mode="delta")
+    T = fgmp.threshold_for_fraction(sc, p)
+    del sc
+    pk, scores = fgmp.quantize_activations(xd, fd, T, S, want_scores=True, score_mode="delta")
+    rng = np.random.default_rng(26)
+    tiles = np.unique(np.concatenate([[0, rows_n // 8 - 1], rng.choice(rows_n // 8, 10, replace=False)]))
+    rows = np.concatenate([np.arange(8 * t, 8 * t + 8) for t in tiles])
+    ridx = torch.from_numpy(rows).to(DEV)
+    want = orc.quantize(xd[ridx].float().cpu().numpy(), f, T, S, score_mode="delta")
+    codes, scales, mask = fgmp.unpack_canonical(pk)
+    assert 0 < int(mask.sum()) < mask.numel()
+    assert np.array_equal(mask[ridx].cpu().numpy(), want["mask"])
+    assert np.array_equal(scales[ridx].cpu().numpy(), want["scales"])
+    assert np.array_equal(codes[ridx].cpu().numpy(), want["codes"])
+    assert np.array_equal(scores[ridx].cpu().numpy().view(np.uint32), want["scores"].view(np.uint32))
+    # the first 2048 rows alone are a tensor of 16384 tiles: the general kernel
+    pk2, scores2 = fgmp.quantize_activations(xd[:2048], fd, T, S, want_scores=True, score_mode="delta")
+    c2, s2, m2 = fgmp.unpack_canonical(pk2)
+    assert torch.equal(c2, codes[:2048]) and torch.equal(s2, scales[:2048]) and torch.equal(m2, mask[:2048])
+    assert torch.equal(scores2, scores[:2048])
+
+
 def test_quantize_activations_fc2_input():
     x = synth.activations(1024, 11008, 0, 5, kind="silu_gate")
     _run_act_case(x, synth.fisher_per_channel(11008, 0, 6), 0.1, "fc2-X", bf16=True)
