@@ -186,10 +186,9 @@ __device__ __forceinline__ void stream_x_block(const StreamArgs &a, int m, int k
 // takes the 4-bit route, the lanes whose block is FP8 then overwrite the result -- with both kinds in
 // nearly every wave, this costs fewer instructions than two exclusive branches.  (The 4-bit route of an
 // FP8 block multiplies by whatever its plane-S byte decodes to; nothing of it survives.)
-__device__ __forceinline__ void st_decode_block(uint2 lw, uint32_t sb, bool hi, uint2 hw, half2_t (&out)[8])
+// s: the block scale in both halves
+__device__ __forceinline__ void st_decode_block(uint2 lw, half2_t s, bool hi, uint2 hw, half2_t (&out)[8])
 {
-    const half2_t s1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(sb, 1.0f, false);
-    const half2_t s = half2_t{s1[0], s1[0]};
     out[0] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 0) * s;
     out[1] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 1) * s;
     out[2] = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(lw.x, 1.0f, 2) * s;
@@ -215,7 +214,9 @@ struct StreamSlot {
     uint32_t s;         // plane S: their two bytes
     u32x2_t m;          // plane M: the tile's mask word
     uint32_t t;         // plane T: first plane-H entry of the tile
-    u32x4_t up;         // plane H: two consecutive entries, from the lane's first FP8 block on (from entry 0 where it has none)
+    u32x4_t up;         // plane H: two consecutive entries -- the second is the entry of the lane's second block where that
+                        // is FP8, the first the entry of its first block where that is FP8
+    uint32_t bits;      // which of the lane's two blocks are FP8 (from the mask, when the plane-H request is made)
 };
 
 // The stream's loads are assembly with hand-counted waits.  Left to the compiler, every wait in the
@@ -577,7 +578,11 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
         t_next = t0 + (uint32_t)__builtin_popcount(s.m[0]) + (uint32_t)__builtin_popcount(s.m[1]);
         if (++h_c == nt) h_c = 0;
         const uint32_t r0 = t0 + (uint32_t)__builtin_popcount(s.m[0] & below_lo) + (uint32_t)__builtin_popcount(s.m[1] & below_hi);
-        st_load_h(s, hbuf, a.off_H + (bits != 0u ? r0 : 0u) * 8u);
+        s.bits = bits;
+        // 16 bytes from one entry before the second block's: that entry lands in the upper half whatever the
+        // first block is, and the first block's, where it is FP8, is the one before it (lanes without FP8 blocks
+        // read neighbouring entries they do not use; at the very start the 8 bytes in front of the plane)
+        st_load_h(s, hbuf, a.off_H - 8u + (r0 + (bits & 1u)) * 8u);
     };
     auto issue_tile = [&](StreamSlot &s) {
         uint32_t t, bytes;
@@ -768,11 +773,11 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
     // elements 32 g + 8 j .. + 7 of the tile), multiply, and close the run after its last tile
     auto consume = [&](StreamSlot &s) {
         half2_t b[16];
-        const uint32_t bits = ((upper ? s.m[1] : s.m[0]) >> sh) & 3u;
-        // (both blocks FP8: their entries are neighbours; one: its entry came first)
-        const bool both = bits == 3u;
-        st_decode_block(make_uint2(s.l[0], s.l[1]), s.s & 0xFFu, bits & 1u, make_uint2(s.up[0], s.up[1]), reinterpret_cast<half2_t(&)[8]>(b[0]));
-        st_decode_block(make_uint2(s.l[2], s.l[3]), s.s >> 8, bits & 2u, make_uint2(both ? s.up[2] : s.up[0], both ? s.up[3] : s.up[1]),
+        const uint32_t bits = s.bits;
+        // (one conversion decodes both scale bytes)
+        const half2_t s01 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(s.s, 1.0f, false);
+        st_decode_block(make_uint2(s.l[0], s.l[1]), half2_t{s01[0], s01[0]}, bits & 1u, make_uint2(s.up[0], s.up[1]), reinterpret_cast<half2_t(&)[8]>(b[0]));
+        st_decode_block(make_uint2(s.l[2], s.l[3]), half2_t{s01[1], s01[1]}, bits & 2u, make_uint2(s.up[2], s.up[3]),
                         reinterpret_cast<half2_t(&)[8]>(b[8]));
         const half8_t *bv = reinterpret_cast<const half8_t *>(b);
         // the slot's registers are free from here on: its next tile is requested before the products, not after
