@@ -794,6 +794,37 @@ def test_decode_step_packed_output_on_random_inputs_is_consistent(M, K, N, dtype
     assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(full), fgmp.unpack_canonical(got)))
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_decode_step_on_random_shapes(seed):
+    """Twelve seeded random decode shapes per seed (1 <= M <= 32, K a multiple of 16 up to 8192 -- mostly not a
+    multiple of the 128-element tile --, N a multiple of 16 up to 6000, FP8 fractions 0 / 0.1 / 0.3 / 1): whatever
+    split of row groups, parts of K and rounds the planner picks, the product from packed activations is within the
+    oracle's tolerance everywhere, the fused step equals it bit for bit, and the step that quantizes its own results
+    in the launch writes the tensor the staged path writes."""
+    rng = np.random.default_rng(7000 + seed)
+    for it in range(12):
+        M = int(rng.integers(1, 33))
+        K = int(rng.integers(1, 513)) * 16
+        N = int(rng.integers(1, 376)) * 16
+        p = float(rng.choice([0.0, 0.1, 0.3, 1.0]))
+        _say(f"random decode shape {seed}/{it}: M={M} K={K} N={N} p={p}")
+        c = _quantized_pair(M, K, N, 7100 + 10 * seed + it, p, per_elem_w=bool(it & 1))
+        Y = fgmp.gemm(c["pX"], c["pW"])
+        _check_gemm(c, Y, label=f"random {M}x{K}x{N}")
+        Yf = fgmp.quant_gemm_fused(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"])
+        assert torch.equal(Y, Yf)
+        s_y = float(Y.abs().max()) / 448.0
+        if s_y > 0:
+            f_n = torch.from_numpy(synth.fisher_per_channel(N, 7100 + it, 9)).to(DEV)
+            _, sc0 = fgmp.quantize_activations(Y, f_n, np.inf, s_y, want_scores=True)
+            T_y = fgmp.threshold_for_fraction(sc0, 0.25)
+            ref, sc_ref = fgmp.quant_gemm_fused_packed_out(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], f_n, T_y, s_y, want_scores=True)
+            got, sc_got = fgmp.quant_gemm_fused_packed_out(c["xd"], c["fxd"], c["Tx"], c["sx"], c["pW"], f_n, T_y, s_y, want_scores=True,
+                                                           epilogue=fgmp.EPILOGUE_ONE_LAUNCH)
+            assert torch.equal(sc_ref, sc_got), "scores of the packed results"
+            assert all(torch.equal(u, v) for u, v in zip(fgmp.unpack_canonical(ref), fgmp.unpack_canonical(got))), "packed results"
+
+
 @pytest.mark.parametrize("M,K,N", [(272, 128, 512), (32, 2048, 1024)])
 def test_packed_results_are_valid_weight_operands(M, K, N):
     """A reader may take a block's plane-H entry from the mask alone (the number of FP8 slots before the block in
