@@ -772,6 +772,14 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
     // one K-tile: decode (b[4 j + i] = halves 2i, 2i+1 of MFMA j's B operand; MFMA j reduces over the K
     // elements 32 g + 8 j .. + 7 of the tile), multiply, and close the run after its last tile
     auto consume = [&](StreamSlot &s) {
+        // (the activation operands of the tile are asked for first: the LDS answers while the tile is decoded)
+        const _Float16 *xc = xrow_p + (kt_b - kt_part0 + con_c) * kTileK;
+        half8_t af[4][MT];
+        if constexpr (MT == 1) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) af[j][0] = *reinterpret_cast<const half8_t *>(xc + 8 * j);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         half2_t b[16];
         const uint32_t bits = s.bits;
         // (one conversion decodes both scale bytes)
@@ -782,14 +790,13 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
         const half8_t *bv = reinterpret_cast<const half8_t *>(b);
         // the slot's registers are free from here on: its next tile is requested before the products, not after
         issue_tile(s);
-        const _Float16 *xc = xrow_p + (kt_b - kt_part0 + con_c) * kTileK;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const half8_t af = *reinterpret_cast<const half8_t *>(xc + mt * 16 * xrow + 8 * j);
-                if (j % 2 == 0) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bv[j], acc[mt], 0, 0, 0);
-                else acc2[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bv[j], acc2[mt], 0, 0, 0);
+                if constexpr (MT != 1) af[j][mt] = *reinterpret_cast<const half8_t *>(xc + mt * 16 * xrow + 8 * j);
+                if (j % 2 == 0) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[j][mt], bv[j], acc[mt], 0, 0, 0);
+                else acc2[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[j][mt], bv[j], acc2[mt], 0, 0, 0);
             }
         }
         if (++con_c >= nt) {
