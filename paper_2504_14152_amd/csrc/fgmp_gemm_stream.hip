@@ -771,15 +771,17 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
     };
     // one K-tile: decode (b[4 j + i] = halves 2i, 2i+1 of MFMA j's B operand; MFMA j reduces over the K
     // elements 32 g + 8 j .. + 7 of the tile), multiply, and close the run after its last tile
-    auto consume = [&](StreamSlot &s) {
-        // (the activation operands of the tile are asked for first: the LDS answers while the tile is decoded)
-        const _Float16 *xc = xrow_p + (kt_b - kt_part0 + con_c) * kTileK;
-        half8_t af[4][MT];
+    // (the activation operands of a tile are asked for before the wait for the tile: the LDS answers meanwhile)
+    auto read_a = [&](half8_t (&af)[4][MT]) {
         if constexpr (MT == 1) {
+            const _Float16 *xc = xrow_p + (kt_b - kt_part0 + con_c) * kTileK;
 #pragma unroll
             for (int j = 0; j < 4; ++j) af[j][0] = *reinterpret_cast<const half8_t *>(xc + 8 * j);
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    auto consume = [&](StreamSlot &s, half8_t (&af)[4][MT]) {
+        const _Float16 *xc = xrow_p + (kt_b - kt_part0 + con_c) * kTileK;
         half2_t b[16];
         const uint32_t bits = s.bits;
         // (one conversion decodes both scale bytes)
@@ -811,9 +813,11 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
 #define ST_STEP(J, T)                                                                 \
     if ((T) < total) {                                                                \
         if constexpr ((T) >= kStFirstH) st_wait_mt<st_step_wait(T)>(ring[((J) + kStHLead) % kStRing]); \
+        half8_t af[4][MT];                                                            \
+        read_a(af);                                                                   \
         st_wait_all<st_step_wait(T)>(ring[J]);                                        \
         if constexpr ((T) >= kStFirstH) issue_h(ring[((J) + kStHLead) % kStRing]);     \
-        consume(ring[J]);                                                             \
+        consume(ring[J], af);                                                         \
     }
         ST_STEP(0, 0) ST_STEP(1, 1) ST_STEP(2, 2) ST_STEP(3, 3)
         ST_STAMP(4);
@@ -821,9 +825,11 @@ __global__ __launch_bounds__(64 * kStWaves) void gemm_stream_kernel(StreamArgs a
 #define ST_LOOP_STEP(J)                                                    \
     if (base + (J) < total) {                                              \
         st_wait_mt<st_step_wait(kStRing + (J))>(ring[((J) + kStHLead) % kStRing]); \
+        half8_t af[4][MT];                                                 \
+        read_a(af);                                                        \
         st_wait_all<st_step_wait(kStRing + (J))>(ring[J]);                 \
         issue_h(ring[((J) + kStHLead) % kStRing]);                         \
-        consume(ring[J]);                                                  \
+        consume(ring[J], af);                                              \
     }
             ST_LOOP_STEP(0) ST_LOOP_STEP(1) ST_LOOP_STEP(2) ST_LOOP_STEP(3)
 #undef ST_LOOP_STEP
